@@ -1,0 +1,322 @@
+"""Plain fp64 CPU oracle for the AT-GRPO policy-loss path.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, obviously-correct statement of
+what the GPU library computes.  It is imported by the tests, by the smoke check and
+by the CPU-baseline leg of the benchmark, and by nothing else; the product path never
+routes through it.  It shares no code with the HIP kernels and does not import the
+package that wraps them.
+
+Everything is written straight from the paper's definitions, in fp64, with numpy.
+Library primitives (matmul, sort, exp/log) serve as single steps; nothing is blocked,
+fused or reordered.  Inputs that live in bf16/fp32 on the device are widened exactly to
+fp64 here and are never re-rounded.
+
+Paper passages followed (arXiv 2510.11062):
+  * group key  g = hash(e, i, t)                      -- Alg. 1 (Phase 1), Sec. 4.1
+                                                        "Agent- and Turn-wise Grouping"
+  * group-relative advantage                           -- Sec. 3 "Group-based RL", Eq. (1)
+  * per-model batch B_m and clipped surrogate          -- Sec. 3, Eq. (2)
+  * response-token credit (reward mask)                -- Sec. 4.1, first paragraph
+  * pi_theta(token) from the LM head                   -- implicit in r(theta) below Eq. (2)
+
+Readings taken where the paper is silent (all are parameters):
+  * F_norm in Eq. (1) is the standard deviation; population (ddof=0) by default; the
+    quotient is (R - mean) / (std + eps_std).  A group whose rewards are all the same
+    fp32 value (including a singleton group) gets advantage exactly 0.
+  * the importance ratio is per token, r_t = exp(logp_t - old_logp_t), and the expectation
+    in Eq. (2) is a masked token mean over the per-model batch ("token_mean"), or, read
+    literally, a mean over responses of per-response token means ("seq_mean_token_mean").
+  * clip flags are decided in log space on the fp32 difference d = fp32(logp) - fp32(old):
+    low  <=> d < fp32(log1p(-eps_low)),  high <=> d > fp32(log1p(eps_high)).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+CLIP_LOW = 1    # bit 0: ratio below 1 - eps_low
+CLIP_HIGH = 2   # bit 1: ratio above 1 + eps_high
+CLIP_ZERO_GRAD = 4  # bit 2: the clipped branch is the one min() selects (no gradient)
+
+
+# --------------------------------------------------------------------------------------
+# S1: group keys and segments  (Alg. 1, "Define group key g <- hash(e, i, t)")
+# --------------------------------------------------------------------------------------
+def group_key(env_id, agent_id, turn_id, n_agent: int, n_turn: int) -> np.ndarray:
+    """Injective packing of (e, i, t): key = (e * n_agent + i) * n_turn + t.
+
+    Any injective hash gives the same partition of the responses; this one also fixes a
+    canonical ORDER of the groups (ascending key) so integer outputs are comparable.
+    """
+    e = np.asarray(env_id, dtype=np.int64)
+    i = np.asarray(agent_id, dtype=np.int64)
+    t = np.asarray(turn_id, dtype=np.int64)
+    return (e * int(n_agent) + i) * int(n_turn) + t
+
+
+def group_segments(key: np.ndarray):
+    """Dense group numbering, CSR offsets and the stable permutation that sorts by key.
+
+    Returns (group_id[R], n_groups, seg_offsets[G+1], perm[R]).  Keys that do not occur
+    (an environment that terminated early) produce no group.
+    """
+    key = np.asarray(key, dtype=np.int64)
+    present = np.unique(key)                      # ascending distinct keys
+    group_id = np.searchsorted(present, key).astype(np.int32)
+    n_groups = int(present.shape[0])
+    counts = np.bincount(group_id, minlength=n_groups)
+    seg_offsets = np.zeros(n_groups + 1, dtype=np.int32)
+    seg_offsets[1:] = np.cumsum(counts)
+    perm = np.argsort(key, kind="stable").astype(np.int32)
+    return group_id, n_groups, seg_offsets, perm
+
+
+# --------------------------------------------------------------------------------------
+# S2: group-relative advantage  (Eq. 1)
+# --------------------------------------------------------------------------------------
+def group_advantage(reward, group_id, n_groups: int, eps_std: float = 1e-6, ddof: int = 0,
+                    norm: str = "std"):
+    """A = (R - mean_g R) / F_norm, per group.  Returns (adv[R], mean[G], std[G]) in fp64.
+
+    norm="std":  F_norm = std + eps_std (std with the given ddof; 0 if n_g - ddof <= 0)
+    norm="none": F_norm = 1
+    Groups whose rewards are all bit-identical fp32 values get A = 0 exactly.
+    """
+    r32 = np.asarray(reward, dtype=np.float32)
+    r = r32.astype(np.float64)
+    gid = np.asarray(group_id, dtype=np.int64)
+    adv = np.zeros(r.shape[0], dtype=np.float64)
+    mean = np.zeros(n_groups, dtype=np.float64)
+    std = np.zeros(n_groups, dtype=np.float64)
+    for g in range(n_groups):
+        members = np.nonzero(gid == g)[0]
+        x = r[members]
+        n = x.shape[0]
+        mu = x.sum() / n
+        dev = x - mu
+        denom = n - ddof
+        sigma = np.sqrt((dev * dev).sum() / denom) if denom > 0 else 0.0
+        mean[g] = mu
+        std[g] = sigma
+        if np.all(r32[members] == r32[members[0]]):
+            mean[g] = x[0]
+            std[g] = 0.0
+            continue                               # adv stays exactly 0
+        if norm == "std":
+            adv[members] = dev / (sigma + eps_std)
+        elif norm == "none":
+            adv[members] = dev
+        else:
+            raise ValueError(norm)
+    return adv, mean, std
+
+
+# --------------------------------------------------------------------------------------
+# S3 + S4: LM-head logits, log-softmax, gather of the sampled token
+# --------------------------------------------------------------------------------------
+def head_logits(hidden, W) -> np.ndarray:
+    """z[t, v] = sum_h hidden[t, h] * W[v, h]   (fp64)."""
+    h = np.asarray(hidden, dtype=np.float64)
+    w = np.asarray(W, dtype=np.float64)
+    return h @ w.T
+
+
+def token_logprob_single(hidden, W, token_id):
+    """log pi(y_t) and log-sum-exp for every row of `hidden` under ONE head.
+
+    Returns (logp[n], lse[n]).
+    """
+    z = head_logits(hidden, W)
+    y = np.asarray(token_id, dtype=np.int64)
+    mx = z.max(axis=1)
+    lse = mx + np.log(np.exp(z - mx[:, None]).sum(axis=1))
+    logp = z[np.arange(z.shape[0]), y] - lse
+    return logp, lse
+
+
+def token_heads(n_tok: int, cu_seqlens, resp_agent=None, head_of_agent=None):
+    """resp_of_tok[t] and head_of_tok[t]: the response owning row t and sigma(agent)."""
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    n_resp = cu.shape[0] - 1
+    resp_of_tok = np.full(n_tok, -1, dtype=np.int64)
+    for r in range(n_resp):
+        resp_of_tok[cu[r]:cu[r + 1]] = r
+    if resp_agent is None or head_of_agent is None:
+        head_of_tok = np.zeros(n_tok, dtype=np.int64)
+    else:
+        head_of_resp = np.asarray(head_of_agent, dtype=np.int64)[np.asarray(resp_agent, dtype=np.int64)]
+        head_of_tok = np.where(resp_of_tok >= 0, head_of_resp[np.maximum(resp_of_tok, 0)], 0)
+    head_of_tok = np.where(resp_of_tok >= 0, head_of_tok, -1)
+    return resp_of_tok, head_of_tok
+
+
+def token_logprob(hidden, W_list, token_id, mask, head_of_tok):
+    """logp, lse for every row; rows with mask 0 (or owned by no response) give 0, 0."""
+    n_tok = np.asarray(hidden).shape[0]
+    m = np.ones(n_tok, dtype=bool) if mask is None else (np.asarray(mask) != 0)
+    logp = np.zeros(n_tok, dtype=np.float64)
+    lse = np.zeros(n_tok, dtype=np.float64)
+    y = np.asarray(token_id)
+    for k, W in enumerate(W_list):
+        rows = np.nonzero(m & (head_of_tok == k))[0]
+        if rows.size == 0:
+            continue
+        lp, ls = token_logprob_single(np.asarray(hidden)[rows], W, y[rows])
+        logp[rows] = lp
+        lse[rows] = ls
+    return logp, lse
+
+
+# --------------------------------------------------------------------------------------
+# S5 + S6: clipped surrogate and masked averaging  (Eq. 2)
+# --------------------------------------------------------------------------------------
+def clip_thresholds(eps_low: float, eps_high: float):
+    """fp32 log-space thresholds lo = log1p(-eps_low), hi = log1p(eps_high)."""
+    el = float(np.float32(eps_low))
+    eh = float(np.float32(eps_high))
+    return np.float32(np.log1p(-el)), np.float32(np.log1p(eh))
+
+
+def token_weights(mask, head_of_tok, resp_of_tok, n_heads: int, agg: str = "token_mean"):
+    """w_t such that loss_m = - sum_t w_t * l_t, plus n_valid[m].
+
+    token_mean:           w_t = mask_t / (number of masked-in tokens routed to head m)
+    seq_mean_token_mean:  w_t = mask_t / (R_m * len_r), len_r = masked-in tokens of the
+                          response, R_m = responses of head m with len_r > 0
+    """
+    n_tok = head_of_tok.shape[0]
+    m = np.ones(n_tok, dtype=bool) if mask is None else (np.asarray(mask) != 0)
+    m = m & (head_of_tok >= 0)
+    w = np.zeros(n_tok, dtype=np.float64)
+    n_valid = np.zeros(n_heads, dtype=np.int64)
+    for k in range(n_heads):
+        sel = m & (head_of_tok == k)
+        n_valid[k] = int(sel.sum())
+        if n_valid[k] == 0:
+            continue
+        if agg == "token_mean":
+            w[sel] = 1.0 / n_valid[k]
+        elif agg == "seq_mean_token_mean":
+            resp = resp_of_tok[sel]
+            ids, lens = np.unique(resp, return_counts=True)
+            len_of = dict(zip(ids.tolist(), lens.tolist()))
+            w[sel] = np.array([1.0 / (ids.shape[0] * len_of[int(r)]) for r in resp])
+        else:
+            raise ValueError(agg)
+    return w, n_valid
+
+
+def surrogate_terms(logp, old_logp, adv_tok, eps_low: float, eps_high: float):
+    """Per-token pieces of Eq. (2).
+
+    Returns (l[n], ratio[n], clip_mask[n] uint8, sel[n] bool) where
+      d     = fp32(logp) - fp32(old_logp)               (one fp32 subtraction)
+      ratio = exp(d)
+      l     = min(ratio * A, clip(ratio, 1 - eps_low, 1 + eps_high) * A)
+      clip_mask bits: CLIP_LOW (d < lo), CLIP_HIGH (d > hi), CLIP_ZERO_GRAD
+      sel   = the unclipped branch is the one min() takes (ties -> unclipped); d l / d logp
+              is ratio * A where sel, 0 elsewhere.
+    """
+    lo32, hi32 = clip_thresholds(eps_low, eps_high)
+    d32 = np.asarray(logp, dtype=np.float64).astype(np.float32) - np.asarray(old_logp, dtype=np.float32)
+    d = d32.astype(np.float64)
+    A = np.asarray(adv_tok, dtype=np.float64)
+    ratio = np.exp(d)
+    el = float(np.float32(eps_low))
+    eh = float(np.float32(eps_high))
+    unclipped = ratio * A
+    clipped = np.clip(ratio, 1.0 - el, 1.0 + eh) * A
+    l = np.minimum(unclipped, clipped)
+    low = d32 < lo32
+    high = d32 > hi32
+    zero_grad = (high & (A > 0)) | (low & (A < 0))
+    clip_mask = (low.astype(np.uint8) * CLIP_LOW) | (high.astype(np.uint8) * CLIP_HIGH) \
+        | (zero_grad.astype(np.uint8) * CLIP_ZERO_GRAD)
+    sel = ~zero_grad
+    return l, ratio, clip_mask, sel
+
+
+def policy_loss_from_logp(logp, old_logp, adv, mask, head_of_tok, resp_of_tok, n_heads: int,
+                          eps_low: float, eps_high: float, agg: str = "token_mean"):
+    """S5 + S6 given log-probs.  Returns (loss[M], clip_mask[n], n_valid[M], w[n], ratio, sel)."""
+    n_tok = head_of_tok.shape[0]
+    w, n_valid = token_weights(mask, head_of_tok, resp_of_tok, n_heads, agg)
+    adv64 = np.asarray(adv, dtype=np.float32).astype(np.float64)
+    adv_tok = np.where(resp_of_tok >= 0, adv64[np.maximum(resp_of_tok, 0)], 0.0)
+    l, ratio, clip_mask, sel = surrogate_terms(logp, old_logp, adv_tok, eps_low, eps_high)
+    valid = w > 0
+    clip_mask = np.where(valid, clip_mask, 0).astype(np.uint8)
+    loss = np.zeros(n_heads, dtype=np.float64)
+    for k in range(n_heads):
+        rows = valid & (head_of_tok == k)
+        loss[k] = -(w[rows] * l[rows]).sum()
+    return loss, clip_mask, n_valid, w, ratio, sel, adv_tok
+
+
+def policy_loss_fwd(hidden, W_list, token_id, mask, cu_seqlens, resp_agent, head_of_agent,
+                    old_logp, adv, eps_low: float, eps_high: float, agg: str = "token_mean"):
+    """S3..S6.  Returns dict(loss, logp, lse, clip_mask, n_valid)."""
+    n_tok = np.asarray(hidden).shape[0]
+    resp_of_tok, head_of_tok = token_heads(n_tok, cu_seqlens, resp_agent, head_of_agent)
+    logp, lse = token_logprob(hidden, W_list, token_id, mask, head_of_tok)
+    loss, clip_mask, n_valid, w, ratio, sel, adv_tok = policy_loss_from_logp(
+        logp, old_logp, adv, mask, head_of_tok, resp_of_tok, len(W_list), eps_low, eps_high, agg)
+    return dict(loss=loss, logp=logp, lse=lse, clip_mask=clip_mask, n_valid=n_valid,
+                w=w, ratio=ratio, sel=sel, adv_tok=adv_tok,
+                resp_of_tok=resp_of_tok, head_of_tok=head_of_tok)
+
+
+# --------------------------------------------------------------------------------------
+# S7 + S8: backward
+# --------------------------------------------------------------------------------------
+def logprob_coefficient(w, adv_tok, ratio, sel, head_of_tok, grad_loss=None):
+    """g_t = d loss_m / d logp_t = - w_t * A_t * ratio_t * [unclipped branch] * grad_loss_m."""
+    g = -w * adv_tok * ratio * sel.astype(np.float64)
+    if grad_loss is not None:
+        gl = np.asarray(grad_loss, dtype=np.float64)
+        g = g * np.where(head_of_tok >= 0, gl[np.maximum(head_of_tok, 0)], 0.0)
+    return g
+
+
+def head_backward_single(hidden, W, token_id, g):
+    """Gradients of sum_t g_t * logp_t w.r.t. hidden rows and W, for ONE head.
+
+    dZ[t, v]      = g_t * (1[v = y_t] - softmax(z_t)[v])
+    dHidden[t, :] = sum_v dZ[t, v] * W[v, :]
+    dW[v, :]      = sum_t dZ[t, v] * hidden[t, :]
+    """
+    h = np.asarray(hidden, dtype=np.float64)
+    w = np.asarray(W, dtype=np.float64)
+    y = np.asarray(token_id, dtype=np.int64)
+    z = h @ w.T
+    mx = z.max(axis=1, keepdims=True)
+    e = np.exp(z - mx)
+    p = e / e.sum(axis=1, keepdims=True)
+    dZ = -p
+    dZ[np.arange(z.shape[0]), y] += 1.0
+    dZ *= np.asarray(g, dtype=np.float64)[:, None]
+    return dZ @ w, dZ.T @ h
+
+
+def policy_loss_bwd(hidden, W_list, token_id, mask, cu_seqlens, resp_agent, head_of_agent,
+                    old_logp, adv, eps_low: float, eps_high: float, agg: str = "token_mean",
+                    grad_loss=None):
+    """S7 + S8.  Returns dict(d_hidden[n_tok, H], dW[list of [V, H]], g[n_tok])."""
+    fwd = policy_loss_fwd(hidden, W_list, token_id, mask, cu_seqlens, resp_agent, head_of_agent,
+                          old_logp, adv, eps_low, eps_high, agg)
+    g = logprob_coefficient(fwd["w"], fwd["adv_tok"], fwd["ratio"], fwd["sel"],
+                            fwd["head_of_tok"], grad_loss)
+    hid = np.asarray(hidden)
+    d_hidden = np.zeros(hid.shape, dtype=np.float64)
+    dW = []
+    y = np.asarray(token_id)
+    for k, W in enumerate(W_list):
+        rows = np.nonzero((fwd["w"] > 0) & (fwd["head_of_tok"] == k))[0]
+        if rows.size == 0:
+            dW.append(np.zeros(np.asarray(W).shape, dtype=np.float64))
+            continue
+        dh, dw = head_backward_single(hid[rows], W, y[rows], g[rows])
+        d_hidden[rows] = dh
+        dW.append(dw)
+    out = dict(fwd)
+    out.update(d_hidden=d_hidden, dW=dW, g=g)
+    return out
