@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Throughput of the AT-GRPO policy-loss hot path on one MI355X.
+
+One step = grouped advantages + policy-loss forward + backward over one synthetic rollout batch
+(all inputs resident in HBM before the timed region).  Prints ONE JSON line:
+tokens/s over the response tokens, the roofline fraction of the dominant kernel (measured with
+HIP events recorded on the launch stream inside the library) and the CPU oracle timed on a small
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2510_11062_amd import api, rollout_standin, synth  # noqa: E402
+
+PEAK = {"bf16": 2500.0, "f32": 157.3}      # dense MFMA TFLOP/s, MI355X data sheet
+
+
+def build_inputs(cfg, dev):
+    st = synth.make_structure(cfg)
+    hidden, W = synth.make_tensors(cfg, st.n_tok, device=dev)
+    u, noise = synth.make_rollout_randoms(cfg, st.n_tok, device=dev)
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    cu = torch.from_numpy(st.cu_seqlens).to(dev)
+    lengths = torch.from_numpy(st.lengths).to(dev)
+    resp_of_tok = torch.repeat_interleave(torch.arange(len(st.lengths), device=dev), cu[1:] - cu[:-1])
+    mask = None if st.mask is None else torch.from_numpy(st.mask).to(dev)
+    valid = torch.ones(st.n_tok, dtype=torch.bool, device=dev) if mask is None else mask.bool()
+    head_of_resp = torch.from_numpy(st.head_of_agent[st.agent_id].astype(np.int64)).to(dev)
+    head_of_tok = head_of_resp[resp_of_tok]
+    token_id, old_logp = rollout_standin.draw_tokens_and_old_logp(hidden, W, head_of_tok, valid, u, noise)
+    del u, noise
+    multi = cfg.n_heads > 1
+    batch = api.Batch(hidden, W, token_id, cu, mask, i32(st.agent_id) if multi else None,
+                      i32(st.head_of_agent) if multi else None)
+    ids = (i32(st.env_id), i32(st.agent_id), i32(st.turn_id), torch.from_numpy(st.reward).to(dev))
+    return st, batch, ids, old_logp, resp_of_tok, valid, lengths
+
+
+def cpu_baseline(cfg, st, batch, old_logp, n_sample):
+    """The CPU oracle (fp64 numpy), timed as it stands on a packed sample of response tokens."""
+    from oracle import at_grpo_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    valid = torch.ones(st.n_tok, dtype=torch.bool) if st.mask is None else torch.from_numpy(st.mask != 0)
+    rows = torch.nonzero(valid).squeeze(1)[:n_sample]
+    dev_rows = rows.to(batch.hidden.device)
+    hidden = batch.hidden[dev_rows].float().cpu().numpy()
+    W = [w.float().cpu().numpy() for w in batch.W[:1]]
+    y = batch.token_id[dev_rows].cpu().numpy()
+    old = old_logp[dev_rows].cpu().numpy()
+    n = hidden.shape[0]
+    cu = np.arange(n + 1, dtype=np.int64)
+    adv = np.random.default_rng(0).standard_normal(n).astype(np.float32)
+    t0 = time.perf_counter()
+    orc.policy_loss_bwd(hidden, W, y, None, cu, None, None, old, adv, cfg.eps_clip, cfg.eps_clip)
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n} response tokens of {cfg.name} on one head, fp64 numpy forward+backward "
+                      f"(one-token responses), {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="C2")
+    ap.add_argument("--cpu-sample", type=int, default=256, help="response tokens given to the CPU oracle (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS[args.config]
+    api.load_library()
+
+    st, batch, ids, old_logp, resp_of_tok, valid, lengths = build_inputs(cfg, dev)
+    env_id, agent_id, turn_id, reward = ids
+    eps = cfg.eps_clip
+
+    d_hidden = torch.empty_like(batch.hidden)
+    dW = [torch.empty(w.shape, dtype=torch.float32, device=dev) for w in batch.W]
+    state = {}
+
+    def step():
+        ga = api.at_grpo_group_advantage(env_id, agent_id, turn_id, reward, cfg.E, cfg.N, cfg.T, want_stats=False)
+        fwd = api.at_grpo_policy_loss_fwd(batch, old_logp, ga["adv"], eps, eps, out=state.get("fwd"))
+        api.at_grpo_policy_loss_bwd(batch, old_logp, ga["adv"], fwd["logp"], fwd["lse"], eps, eps,
+                                    dW=dW, d_hidden=d_hidden)
+        state["fwd"], state["ga"] = fwd, ga
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    api.at_grpo_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = api.at_grpo_profile_read()
+    api.at_grpo_profile_enable(False)
+
+    n_valid = int(valid.sum().item())
+    fwd, ga = state["fwd"], state["ga"]
+    err = api.error_word(fwd["workspace"])
+    # rows that carry gradient: participating, advantage != 0, not on the clipped branch
+    A_tok = ga["adv"][resp_of_tok]
+    n_grad = int((valid & (A_tok != 0) & ((fwd["clip_mask"] & 4) == 0)).sum().item())
+    ms_per_step = elapsed / args.steps * 1e3
+    tokens_per_s = n_valid / (elapsed / args.steps)
+
+    hv2 = 2.0 * cfg.H * cfg.V
+    flops = {"head_fwd": hv2 * n_valid, "head_dz": hv2 * n_grad, "head_dh": hv2 * n_grad, "head_dw": hv2 * n_grad}
+    kern = max(flops, key=lambda k: prof[k][1])
+    kern_ms = prof[kern][1] / args.steps
+    achieved = flops[kern] / (kern_ms * 1e-3) / 1e12
+    peak = PEAK[cfg.dtype]
+    all_gemm_ms = sum(prof[k][1] for k in flops) / args.steps
+    all_gemm_tflops = sum(flops.values()) / (all_gemm_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "policy-loss fwd+bwd tokens/sec at V=151936; MFMA util % and HBM GB/s",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: H={cfg.H} V={cfg.V} heads={cfg.n_heads} "
+                               f"E{cfg.E}xN{cfg.N}xT{cfg.T}xK{cfg.K}={st.cfg.n_resp} responses, "
+                               f"{n_valid} response tokens in {st.n_tok} rows"
+                               f"{' (padded + mask)' if cfg.padded else ' (packed)'}",
+                   "rows_with_gradient": n_grad, "device_error_word": err},
+        "roofline": {"bound": "mfma", "kernel": kern, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None,
+                     "kernel_ms_per_step": kern_ms, "launches_per_step": prof[kern][0] / args.steps,
+                     "all_head_contractions_tflops": all_gemm_tflops,
+                     "all_head_contractions_frac": all_gemm_tflops / peak},
+        "kernel_ms_per_step": {k: v[1] / args.steps for k, v in prof.items()},
+    }
+    if args.cpu_sample > 0:
+        out["cpu_baseline"] = cpu_baseline(cfg, st, batch, old_logp, args.cpu_sample)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,208 @@
+/*
+ * at_grpo.h -- C ABI of the MI355X (gfx950) AT-GRPO policy-loss library.
+ *
+ * The library computes, on one GPU, the per-token policy loss of AT-GRPO
+ * (arXiv 2510.11062): agent- and turn-wise grouped advantages (Alg. 1, Phase 1; Eq. 1),
+ * log pi_theta(token) from the LM head (the ratio below Eq. 2), the clipped surrogate with
+ * masked averaging per policy (Eq. 2; per-model batches B_m of Sec. 3) and its gradients
+ * with respect to the final hidden states and the head weights.
+ *
+ * Conventions common to every call
+ *   - Pointers are DEVICE pointers unless the comment says "host".  The caller owns every
+ *     buffer; the library never allocates, frees or keeps a pointer after the call returns.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t cast to void*; NULL = default
+ *     stream).  No call synchronises with the host.  Scalar results live in device memory.
+ *   - `workspace` is caller-provided device scratch of at least at_grpo_workspace_bytes()
+ *     bytes, 256-byte aligned.  Its first int32 is an error word: 0, or the bit-or of
+ *     AT_GRPO_DATA_* flags raised by data that is only visible on the device.  Offending
+ *     elements are treated as masked out.  Read it after synchronising the stream.
+ *   - Return value: an at_grpo_status.  Argument errors are detected on the host before
+ *     anything is launched; nothing is thrown and nothing aborts.
+ *   - Matrices are row-major and dense.  `hidden` is [n_tok, H]; each head W is [V, H].
+ *   - dtype AT_GRPO_BF16 requires H % 64 == 0; AT_GRPO_F32 requires H % 32 == 0.
+ */
+#ifndef AT_GRPO_H_
+#define AT_GRPO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AT_GRPO_OK = 0,
+  AT_GRPO_EINVAL = 1,       /* null pointer, non-positive size, inconsistent arguments */
+  AT_GRPO_EUNSUPPORTED = 2, /* dtype / shape the kernels do not cover                 */
+  AT_GRPO_EWORKSPACE = 3,   /* workspace missing, misaligned or too small             */
+  AT_GRPO_EHIP = 4          /* a HIP runtime call or kernel launch failed             */
+} at_grpo_status;
+
+typedef enum { AT_GRPO_F32 = 0, AT_GRPO_BF16 = 1 } at_grpo_dtype;
+
+/* How Eq. (2)'s expectation over the per-model batch is taken (the paper writes a mean over
+ * groups and candidates; credit is per response token, Sec. 4.1):
+ *   TOKEN_MEAN           loss_m = -(1/n_m) sum_t l_t          over the n_m response tokens of B_m
+ *   SEQ_MEAN_TOKEN_MEAN  loss_m = -(1/R_m) sum_r (1/len_r) sum_{t in r} l_t                  */
+typedef enum { AT_GRPO_AGG_TOKEN_MEAN = 0, AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN = 1 } at_grpo_agg;
+
+/* F_norm of Eq. (1): the group's standard deviation (plus eps_std), or 1. */
+typedef enum { AT_GRPO_NORM_STD = 0, AT_GRPO_NORM_NONE = 1 } at_grpo_norm;
+
+/* Bits of the device error word (workspace[0]). */
+enum {
+  AT_GRPO_DATA_ID_RANGE = 1,     /* env/agent/turn id outside its extent              */
+  AT_GRPO_DATA_REWARD = 2,       /* non-finite reward                                 */
+  AT_GRPO_DATA_TOKEN_RANGE = 4,  /* token_id outside [0, V) on an unmasked row        */
+  AT_GRPO_DATA_SEQLENS = 8,      /* cu_seqlens not monotone within [0, n_tok]         */
+  AT_GRPO_DATA_AGENT_RANGE = 16  /* resp_agent / head_of_agent entry out of range     */
+};
+
+/* Bits of clip_mask[t] (Eq. 2's clip, decided in log space on d = logp - old_logp, one fp32
+ * subtraction, against lo = (float)log1p(-eps_low) and hi = (float)log1p(eps_high)). */
+enum {
+  AT_GRPO_CLIP_LOW = 1,       /* d < lo : ratio below 1 - eps_low                    */
+  AT_GRPO_CLIP_HIGH = 2,      /* d > hi : ratio above 1 + eps_high                   */
+  AT_GRPO_CLIP_ZERO_GRAD = 4  /* min() selects the clipped branch: no gradient       */
+};
+
+/* Which call a workspace is sized for. */
+typedef enum {
+  AT_GRPO_CALL_GROUP_ADVANTAGE = 0,
+  AT_GRPO_CALL_TOKEN_LOGPROB = 1,
+  AT_GRPO_CALL_POLICY_LOSS_FWD = 2,
+  AT_GRPO_CALL_POLICY_LOSS_BWD = 3,
+  AT_GRPO_CALL_SURROGATE = 4
+} at_grpo_call;
+
+/*
+ * A batch of rollout tokens (Alg. 1 Phase 2: the per-model batches B_m, all models at once).
+ * Row t of `hidden` is the final hidden state that predicts token_id[t].  Response r owns rows
+ * [cu_seqlens[r], cu_seqlens[r+1]); rows owned by no response, and rows with mask 0, take no
+ * part (packed layout: mask == NULL; padded layout: fixed-size slots plus mask).  With
+ * n_heads > 1 the rows of response r go to head head_of_agent[resp_agent[r]] (the role
+ * mapping sigma of Sec. 3); with n_heads == 1 both arrays may be NULL.
+ */
+typedef struct {
+  int32_t dtype;             /* at_grpo_dtype of hidden and W                            */
+  int32_t H, V, n_heads;     /* n_heads in [1, 16]                                       */
+  int64_t n_tok;             /* rows of hidden / token_id / mask (padding included)      */
+  int32_t n_resp;            /* R                                                        */
+  int32_t n_agent;           /* length of head_of_agent (ignored if n_heads == 1)        */
+  const int64_t* cu_seqlens; /* [R+1] device                                             */
+  const void* hidden;        /* [n_tok, H] device                                        */
+  const void* const* W;      /* HOST array of n_heads device pointers, each [V, H]       */
+  const int32_t* token_id;   /* [n_tok] device, sampled token, 0 <= id < V               */
+  const uint8_t* mask;       /* [n_tok] device or NULL (all ones)                        */
+  const int32_t* resp_agent; /* [R] device or NULL                                       */
+  const int32_t* head_of_agent; /* [n_agent] device or NULL                              */
+} at_grpo_batch;
+
+/*
+ * Agent- and turn-wise grouping and group-relative advantages.
+ * Alg. 1 ("Define group key g <- hash(e, i, t) and compute advantages"), Sec. 4.1
+ * "Agent- and Turn-wise Grouping", Eq. (1).
+ *
+ * key(r) = (env_id[r] * n_agent + agent_id[r]) * n_turn + turn_id[r]; groups are numbered
+ * densely in ascending key order; keys that do not occur produce no group.
+ *   group_id[R]      dense group of each response (-1 for a response with an id out of range)
+ *   n_groups[1]      G
+ *   seg_offsets[G+1] CSR offsets into perm; the buffer must hold min(R, n_env*n_agent*n_turn)+1
+ *   perm[R]          responses sorted by key, ties in ascending original index (stable)
+ *   adv[R]           (reward - mean_g) / (std_g + eps_std)   [NORM_STD]   or reward - mean_g
+ *                    [NORM_NONE]; std uses divisor n_g - ddof (0 if that is <= 0); a group
+ *                    whose rewards are all the same fp32 value gets exactly 0
+ *   group_mean[G], group_std[G]  optional (NULL to skip)
+ * ddof is 0 or 1.  Arithmetic is fp32, sequential in perm order inside a group, hence
+ * deterministic.
+ */
+int at_grpo_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn,
+                            const int32_t* env_id, const int32_t* agent_id, const int32_t* turn_id,
+                            const float* reward, float eps_std, int32_t ddof, int32_t norm,
+                            int32_t* group_id, int32_t* n_groups, int32_t* seg_offsets,
+                            int32_t* perm, float* adv, float* group_mean, float* group_std,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * log pi_theta(token_id[t]) and the log-sum-exp of the head logits for every participating row
+ * (the policy probability inside r(theta) below Eq. 2).  Logits z[t, v] = <hidden[t], W_m[v]>
+ * are produced tile by tile on the matrix cores and reduced on the fly; they are never written
+ * to memory.  Rows that take no part get logp = lse = 0.
+ *   logp[n_tok], lse[n_tok] (lse may be NULL)
+ */
+int at_grpo_token_logprob(const at_grpo_batch* batch, float* logp, float* lse,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Clipped surrogate of Eq. (2) given log-probs (the stage after the head):
+ *   d_t = logp_t - old_logp_t,  r_t = exp(d_t),  A_t = adv[response of t]
+ *   l_t = min(r_t A_t, clip(r_t, 1 - eps_low, 1 + eps_high) A_t)
+ *   loss[m] = - sum_{t in B_m} w_t l_t      (w_t per `agg`)
+ *   clip_mask[n_tok], n_valid[n_heads] (participating rows per head)
+ * Only the batch's layout fields are used (n_tok, n_resp, cu_seqlens, mask, token_id for the
+ * range check, resp_agent, head_of_agent, n_heads, V); hidden and W may be NULL.
+ * The reduction is a fixed-order tree: results are bit-reproducible.
+ */
+int at_grpo_surrogate_from_logp(const at_grpo_batch* batch, const float* logp, const float* old_logp,
+                                const float* adv, float eps_low, float eps_high, int32_t agg,
+                                float* loss, uint8_t* clip_mask, int32_t* n_valid,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Forward of the policy loss: at_grpo_token_logprob followed by at_grpo_surrogate_from_logp.
+ * Outputs logp[n_tok], lse[n_tok] (both are needed by the backward), loss[n_heads],
+ * clip_mask[n_tok], n_valid[n_heads].
+ */
+int at_grpo_policy_loss_fwd(const at_grpo_batch* batch, const float* old_logp, const float* adv,
+                            float eps_low, float eps_high, int32_t agg,
+                            float* loss, float* logp, float* lse, uint8_t* clip_mask, int32_t* n_valid,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward of sum_m grad_loss[m] * loss[m] (grad_loss == NULL means all ones):
+ *   g_t = -w_t A_t r_t [unclipped branch selected] grad_loss[m]
+ *   dZ[t, v]     = g_t (1[v = token_id[t]] - exp(z[t, v] - lse_t))     (logits recomputed)
+ *   d_hidden[t]  = sum_v dZ[t, v] W_m[v]          dtype of hidden, [n_tok, H]; rows that take
+ *                                                  no part or have g_t = 0 are exactly 0
+ *   dW[m][v]     = sum_t dZ[t, v] hidden[t]       fp32 [V, H] per head; dW is a HOST array of
+ *                                                  n_heads device pointers; overwritten, or
+ *                                                  added to when accumulate_dW != 0
+ * logp and lse are the forward's outputs.  Rows with g_t = 0 are skipped entirely.
+ */
+int at_grpo_policy_loss_bwd(const at_grpo_batch* batch, const float* old_logp, const float* adv,
+                            const float* logp, const float* lse,
+                            float eps_low, float eps_high, int32_t agg, const float* grad_loss,
+                            void* d_hidden, float* const* dW, int32_t accumulate_dW,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Bytes of workspace a call needs.  `batch` may be NULL for AT_GRPO_CALL_GROUP_ADVANTAGE; the
+ * id extents are ignored for the other calls.  Only sizes are read from `batch` (H, V, n_heads,
+ * dtype, n_tok, n_resp); no pointer in it is dereferenced.  Returns 0 on invalid arguments.
+ */
+size_t at_grpo_workspace_bytes(int32_t which_call, const at_grpo_batch* batch, int32_t n_resp,
+                               int32_t n_env, int32_t n_agent, int32_t n_turn);
+
+/* Static description of a status code. */
+const char* at_grpo_status_string(int32_t status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int32_t at_grpo_version(void);
+
+/*
+ * Optional per-kernel timing with HIP events recorded on the call's stream (a measurement aid,
+ * off by default; it keeps process-wide state and is not thread-safe).
+ *   at_grpo_profile_enable(1) starts recording, (0) stops and drops what was recorded.
+ *   at_grpo_profile_read synchronises the recorded events and returns, for kernel class
+ *   `which` (0 .. at_grpo_profile_classes()-1), the number of launches and their total
+ *   duration in milliseconds since recording started; the name is a static string.
+ */
+int at_grpo_profile_enable(int32_t on);
+int32_t at_grpo_profile_classes(void);
+int at_grpo_profile_read(int32_t which, const char** name, int64_t* launches, double* total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AT_GRPO_H_ */

@@ -1,0 +1,332 @@
+// C ABI entry points of the AT-GRPO policy-loss library: argument checks, workspace planning and
+// the order in which the kernels are enqueued.  No call synchronises with the host.
+#include <vector>
+
+#include "common.hpp"
+#include "head_kernels.hpp"
+#include "token_kernels.hpp"
+
+namespace atg {
+
+size_t group_advantage_workspace(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn);
+
+// ---- timing aid --------------------------------------------------------------------------------
+namespace {
+struct ProfState {
+  bool on = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> ev[PROF_N];
+};
+ProfState g_prof;
+const char* const kProfNames[PROF_N] = {"group_advantage", "token_prep", "head_fwd", "lse_combine",
+                                        "surrogate", "coef", "transpose", "head_dz", "head_dh",
+                                        "head_dw", "fill"};
+}  // namespace
+
+void prof_begin(int cls, hipStream_t s) {
+  if (!g_prof.on) return;
+  hipEvent_t a = nullptr, b = nullptr;
+  if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+  (void)hipEventRecord(a, s);
+  g_prof.ev[cls].emplace_back(a, b);
+}
+
+void prof_end(int cls, hipStream_t s) {
+  if (!g_prof.on || g_prof.ev[cls].empty()) return;
+  (void)hipEventRecord(g_prof.ev[cls].back().second, s);
+}
+
+int device_cu_count() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    cached[dev] = v;
+  }
+  return cached[dev];
+}
+
+namespace {
+
+constexpr int kMaxChunkTokens = 32768;
+constexpr size_t kDzBudgetBytes = size_t{10} << 30;   // per orientation
+
+struct Plan {
+  TokenLayout L;
+  TokenScratch S;
+  HeadGeom g;
+  int n_chunks;      // super-chunks per head in the worst case (all rows on one head)
+  float* part_m;
+  float* part_s;
+  float* zy;
+  float* coef;
+  void* Wt;
+  void* hT;
+  void* dZ;
+  void* dZt;
+};
+
+int check_layout(const at_grpo_batch* b, bool need_tensors) {
+  if (!b) return AT_GRPO_EINVAL;
+  if (b->n_tok <= 0 || b->n_resp <= 0 || b->V <= 0) return AT_GRPO_EINVAL;
+  if (b->n_heads < 1 || b->n_heads > kMaxHeads) return AT_GRPO_EINVAL;
+  if (b->n_tok > int64_t{0x7fffff00}) return AT_GRPO_EUNSUPPORTED;
+  if (need_tensors) {
+    if (b->dtype != AT_GRPO_F32 && b->dtype != AT_GRPO_BF16) return AT_GRPO_EUNSUPPORTED;
+    if (b->H <= 0) return AT_GRPO_EINVAL;
+    const int esize = b->dtype == AT_GRPO_BF16 ? 2 : 4;
+    if ((static_cast<int64_t>(b->H) * esize) % 128 != 0) return AT_GRPO_EUNSUPPORTED;
+  }
+  return AT_GRPO_OK;
+}
+
+int check_pointers(const at_grpo_batch* b, bool need_tensors) {
+  if (!b->cu_seqlens) return AT_GRPO_EINVAL;
+  if (b->n_heads > 1 && (!b->resp_agent || !b->head_of_agent || b->n_agent <= 0)) return AT_GRPO_EINVAL;
+  if (need_tensors) {
+    if (!b->hidden || !b->W || !b->token_id) return AT_GRPO_EINVAL;
+    if (reinterpret_cast<uintptr_t>(b->hidden) & 15) return AT_GRPO_EINVAL;
+    for (int m = 0; m < b->n_heads; ++m)
+      if (!b->W[m] || (reinterpret_cast<uintptr_t>(b->W[m]) & 15)) return AT_GRPO_EINVAL;
+  }
+  return AT_GRPO_OK;
+}
+
+// Lays the workspace out.  Only sizes are read from the batch.
+void make_plan(const at_grpo_batch* b, int call, WsAlloc& ws, Plan* p) {
+  const int64_t n_tok = b->n_tok;
+  const int M = b->n_heads;
+  p->L.n_tok = n_tok;
+  p->L.n_resp = b->n_resp;
+  p->L.n_heads = M;
+  p->L.n_agent = b->n_agent;
+  p->L.V = b->V;
+  p->L.cu_seqlens = b->cu_seqlens;
+  p->L.token_id = b->token_id;
+  p->L.mask = b->mask;
+  p->L.resp_agent = b->resp_agent;
+  p->L.head_of_agent = b->head_of_agent;
+
+  TokenScratch& S = p->S;
+  S.n_blk = ceil_div(n_tok, kTokPerBlock);
+  S.n_blk256 = ceil_div(n_tok, 256);
+  S.err = ws.take<int32_t>(64);
+  S.cnt = ws.take<int32_t>(kMaxHeads);
+  S.resp_cnt = ws.take<int32_t>(kMaxHeads);
+  S.resp_of_tok = ws.take<int32_t>(static_cast<size_t>(n_tok));
+  S.flag = ws.take<int32_t>(static_cast<size_t>(n_tok));
+  S.blk_cnt = ws.take<int32_t>(static_cast<size_t>(M * S.n_blk));
+  S.blk_off = ws.take<int32_t>(static_cast<size_t>(M * S.n_blk));
+  S.resp_len = ws.take<int32_t>(static_cast<size_t>(b->n_resp));
+  S.blk_loss = ws.take<float>(static_cast<size_t>(M * S.n_blk256));
+  const bool heads = call != AT_GRPO_CALL_SURROGATE;
+  S.idx = heads ? ws.take<int32_t>(static_cast<size_t>(M) * static_cast<size_t>(n_tok)) : nullptr;
+  if (!heads) return;
+
+  HeadGeom& g = p->g;
+  g.dtype = b->dtype;
+  g.H = b->H;
+  g.V = b->V;
+  g.esize = b->dtype == AT_GRPO_BF16 ? 2 : 4;
+  g.Vp = static_cast<int>(round_up(static_cast<size_t>(b->V), 64));
+  g.n_vtiles = static_cast<int>(ceil_div(b->V, 256));
+  int64_t tc = static_cast<int64_t>(round_up(static_cast<size_t>(n_tok), 256));
+  if (tc > kMaxChunkTokens) tc = kMaxChunkTokens;
+  if (call == AT_GRPO_CALL_POLICY_LOSS_BWD) {
+    int64_t cap = static_cast<int64_t>(kDzBudgetBytes / (static_cast<size_t>(g.Vp) * g.esize)) / 256 * 256;
+    if (cap < 256) cap = 256;
+    if (tc > cap) tc = cap;
+  }
+  g.TC = static_cast<int>(tc);
+  p->n_chunks = static_cast<int>(ceil_div(n_tok, tc));
+
+  if (call == AT_GRPO_CALL_TOKEN_LOGPROB || call == AT_GRPO_CALL_POLICY_LOSS_FWD) {
+    const size_t np = static_cast<size_t>(2 * g.n_vtiles) * static_cast<size_t>(g.TC);
+    p->part_m = ws.take<float>(np);
+    p->part_s = ws.take<float>(np);
+    p->zy = ws.take<float>(static_cast<size_t>(g.TC));
+  }
+  if (call == AT_GRPO_CALL_POLICY_LOSS_BWD) {
+    p->coef = ws.take<float>(static_cast<size_t>(n_tok));
+    p->Wt = ws.take<char>(static_cast<size_t>(g.H) * g.Vp * g.esize);
+    p->hT = ws.take<char>(static_cast<size_t>(g.H) * g.TC * g.esize);
+    p->dZ = ws.take<char>(static_cast<size_t>(g.TC) * g.Vp * g.esize);
+    p->dZt = ws.take<char>(static_cast<size_t>(g.V) * g.TC * g.esize);
+  }
+}
+
+int check_workspace(void* workspace, size_t have, size_t need) {
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || have < need) return AT_GRPO_EWORKSPACE;
+  return AT_GRPO_OK;
+}
+
+int enqueue_logprob(const at_grpo_batch* b, const Plan& p, float* logp, float* lse, hipStream_t s) {
+  ATG_TRY(launch_route(p.L, p.S, s));
+  ATG_TRY(launch_compact(p.L, p.S, true, s));
+  ATG_TRY(launch_zero_nonparticipating(p.L, p.S, logp, lse, s));
+  for (int m = 0; m < b->n_heads; ++m) {
+    for (int c = 0; c < p.n_chunks; ++c) {
+      const HeadChunk ch{p.S.idx + static_cast<size_t>(m) * p.L.n_tok, p.S.cnt + m, c * p.g.TC};
+      ATG_TRY(launch_head_fwd(p.g, ch, b->hidden, b->W[m], b->token_id, p.part_m, p.part_s, p.zy, s));
+      ATG_TRY(launch_lse_combine(p.g, ch, p.part_m, p.part_s, p.zy, logp, lse, s));
+    }
+  }
+  return AT_GRPO_OK;
+}
+
+bool agg_ok(int agg) { return agg == AT_GRPO_AGG_TOKEN_MEAN || agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN; }
+bool eps_ok(float lo, float hi) { return lo >= 0.f && lo < 1.f && hi >= 0.f; }
+
+}  // namespace
+}  // namespace atg
+
+using namespace atg;
+
+extern "C" size_t at_grpo_workspace_bytes(int32_t which_call, const at_grpo_batch* batch, int32_t n_resp,
+                                          int32_t n_env, int32_t n_agent, int32_t n_turn) {
+  if (which_call == AT_GRPO_CALL_GROUP_ADVANTAGE)
+    return group_advantage_workspace(n_resp, n_env, n_agent, n_turn);
+  if (which_call < AT_GRPO_CALL_TOKEN_LOGPROB || which_call > AT_GRPO_CALL_SURROGATE) return 0;
+  const bool tensors = which_call != AT_GRPO_CALL_SURROGATE;
+  if (check_layout(batch, tensors) != AT_GRPO_OK) return 0;
+  WsAlloc ws(nullptr);
+  Plan p{};
+  make_plan(batch, which_call, ws, &p);
+  return ws.bytes();
+}
+
+extern "C" int at_grpo_token_logprob(const at_grpo_batch* batch, float* logp, float* lse, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream) {
+  ATG_TRY(check_layout(batch, true));
+  ATG_TRY(check_pointers(batch, true));
+  if (!logp) return AT_GRPO_EINVAL;
+  WsAlloc ws(workspace);
+  Plan p{};
+  make_plan(batch, AT_GRPO_CALL_TOKEN_LOGPROB, ws, &p);
+  ATG_TRY(check_workspace(workspace, workspace_bytes, ws.bytes()));
+  return enqueue_logprob(batch, p, logp, lse, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int at_grpo_surrogate_from_logp(const at_grpo_batch* batch, const float* logp,
+                                           const float* old_logp, const float* adv, float eps_low,
+                                           float eps_high, int32_t agg, float* loss, uint8_t* clip_mask,
+                                           int32_t* n_valid, void* workspace, size_t workspace_bytes,
+                                           void* hip_stream) {
+  ATG_TRY(check_layout(batch, false));
+  ATG_TRY(check_pointers(batch, false));
+  if (!logp || !old_logp || !adv || !loss) return AT_GRPO_EINVAL;
+  if (!agg_ok(agg) || !eps_ok(eps_low, eps_high)) return AT_GRPO_EINVAL;
+  WsAlloc ws(workspace);
+  Plan p{};
+  make_plan(batch, AT_GRPO_CALL_SURROGATE, ws, &p);
+  ATG_TRY(check_workspace(workspace, workspace_bytes, ws.bytes()));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  ATG_TRY(launch_route(p.L, p.S, s));
+  ATG_TRY(launch_compact(p.L, p.S, false, s));
+  if (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN) ATG_TRY(launch_resp_len(p.L, p.S, s));
+  return launch_surrogate(p.L, p.S, logp, old_logp, adv, eps_low, eps_high, agg, loss, clip_mask, n_valid, s);
+}
+
+extern "C" int at_grpo_policy_loss_fwd(const at_grpo_batch* batch, const float* old_logp, const float* adv,
+                                       float eps_low, float eps_high, int32_t agg, float* loss, float* logp,
+                                       float* lse, uint8_t* clip_mask, int32_t* n_valid, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream) {
+  ATG_TRY(check_layout(batch, true));
+  ATG_TRY(check_pointers(batch, true));
+  if (!old_logp || !adv || !loss || !logp || !lse) return AT_GRPO_EINVAL;
+  if (!agg_ok(agg) || !eps_ok(eps_low, eps_high)) return AT_GRPO_EINVAL;
+  WsAlloc ws(workspace);
+  Plan p{};
+  make_plan(batch, AT_GRPO_CALL_POLICY_LOSS_FWD, ws, &p);
+  ATG_TRY(check_workspace(workspace, workspace_bytes, ws.bytes()));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  ATG_TRY(enqueue_logprob(batch, p, logp, lse, s));
+  if (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN) ATG_TRY(launch_resp_len(p.L, p.S, s));
+  return launch_surrogate(p.L, p.S, logp, old_logp, adv, eps_low, eps_high, agg, loss, clip_mask, n_valid, s);
+}
+
+extern "C" int at_grpo_policy_loss_bwd(const at_grpo_batch* batch, const float* old_logp, const float* adv,
+                                       const float* logp, const float* lse, float eps_low, float eps_high,
+                                       int32_t agg, const float* grad_loss, void* d_hidden,
+                                       float* const* dW, int32_t accumulate_dW, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream) {
+  ATG_TRY(check_layout(batch, true));
+  ATG_TRY(check_pointers(batch, true));
+  if (!old_logp || !adv || !logp || !lse || !d_hidden || !dW) return AT_GRPO_EINVAL;
+  if (reinterpret_cast<uintptr_t>(d_hidden) & 15) return AT_GRPO_EINVAL;
+  for (int m = 0; m < batch->n_heads; ++m)
+    if (!dW[m]) return AT_GRPO_EINVAL;
+  if (!agg_ok(agg) || !eps_ok(eps_low, eps_high)) return AT_GRPO_EINVAL;
+  WsAlloc ws(workspace);
+  Plan p{};
+  make_plan(batch, AT_GRPO_CALL_POLICY_LOSS_BWD, ws, &p);
+  ATG_TRY(check_workspace(workspace, workspace_bytes, ws.bytes()));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  // participation and weights, then the coefficient; rows with g_t = 0 drop out of the lists
+  ATG_TRY(launch_route(p.L, p.S, s));
+  ATG_TRY(launch_compact(p.L, p.S, false, s));
+  if (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN) ATG_TRY(launch_resp_len(p.L, p.S, s));
+  ATG_TRY(launch_coef(p.L, p.S, logp, old_logp, adv, eps_low, eps_high, agg, grad_loss, p.coef, s));
+  ATG_TRY(launch_compact(p.L, p.S, true, s));
+  ATG_TRY(launch_fill_bytes16(d_hidden, p.L.n_tok * static_cast<int64_t>(p.g.H) * p.g.esize, s));
+
+  for (int m = 0; m < batch->n_heads; ++m) {
+    ATG_TRY(launch_transpose_w(p.g, batch->W[m], p.Wt, s));
+    for (int c = 0; c < p.n_chunks; ++c) {
+      const HeadChunk ch{p.S.idx + static_cast<size_t>(m) * p.L.n_tok, p.S.cnt + m, c * p.g.TC};
+      ATG_TRY(launch_gather_transpose_hidden(p.g, ch, batch->hidden, p.hT, s));
+      ATG_TRY(launch_head_dz(p.g, ch, batch->hidden, batch->W[m], batch->token_id, lse, p.coef, p.dZ,
+                             p.dZt, s));
+      ATG_TRY(launch_head_dh(p.g, ch, p.dZ, p.Wt, d_hidden, s));
+      ATG_TRY(launch_head_dw(p.g, ch, p.dZt, p.hT, dW[m], (accumulate_dW != 0 || c > 0) ? 1 : 0,
+                             c == 0 ? 1 : 0, s));
+    }
+  }
+  return AT_GRPO_OK;
+}
+
+extern "C" const char* at_grpo_status_string(int32_t status) {
+  switch (status) {
+    case AT_GRPO_OK: return "ok";
+    case AT_GRPO_EINVAL: return "invalid argument";
+    case AT_GRPO_EUNSUPPORTED: return "unsupported dtype or shape";
+    case AT_GRPO_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case AT_GRPO_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int32_t at_grpo_version(void) { return 100; }
+
+extern "C" int at_grpo_profile_enable(int32_t on) {
+  for (int c = 0; c < PROF_N; ++c) {
+    for (auto& e : g_prof.ev[c]) {
+      (void)hipEventDestroy(e.first);
+      (void)hipEventDestroy(e.second);
+    }
+    g_prof.ev[c].clear();
+  }
+  g_prof.on = on != 0;
+  return AT_GRPO_OK;
+}
+
+extern "C" int32_t at_grpo_profile_classes(void) { return PROF_N; }
+
+extern "C" int at_grpo_profile_read(int32_t which, const char** name, int64_t* launches, double* total_ms) {
+  if (which < 0 || which >= PROF_N || !launches || !total_ms) return AT_GRPO_EINVAL;
+  if (name) *name = kProfNames[which];
+  double tot = 0.0;
+  int64_t n = 0;
+  for (auto& e : g_prof.ev[which]) {
+    ATG_HIP_TRY(hipEventSynchronize(e.second));
+    float ms = 0.f;
+    ATG_HIP_TRY(hipEventElapsedTime(&ms, e.first, e.second));
+    tot += ms;
+    ++n;
+  }
+  *launches = n;
+  *total_ms = tot;
+  return AT_GRPO_OK;
+}

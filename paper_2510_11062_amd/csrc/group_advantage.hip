@@ -1,0 +1,371 @@
+// Agent- and turn-wise grouping and group-relative advantages (gfx950).
+//
+// Alg. 1 of the paper keys every sampled candidate by g = hash(e, i, t); Eq. (1) normalises the
+// rewards inside each group.  Here the key is the injective packing
+//   key = (e * n_agent + i) * n_turn + t,
+// groups are numbered densely in ascending key order, and the responses of a group are listed in
+// ascending original index (a stable sort by key).  Pipeline: histogram over the key space ->
+// exclusive scans (present keys -> dense ids, member counts -> CSR offsets) -> scatter through a
+// per-group cursor (arrival order is arbitrary) -> per-group ordering of the segment and the
+// fp32 statistics.  The final ordering makes every output deterministic.
+#include "common.hpp"
+
+namespace atg {
+
+namespace {
+
+constexpr int kKeysPerBlock = 2048;
+constexpr int kSmallGroup = 16;
+
+struct GaArgs {
+  int32_t n_resp, n_env, n_agent, n_turn;
+  const int32_t* env_id;
+  const int32_t* agent_id;
+  const int32_t* turn_id;
+  const float* reward;
+};
+
+__device__ __forceinline__ int64_t key_of(const GaArgs& a, int r, bool* ok) {
+  const int e = a.env_id[r], i = a.agent_id[r], t = a.turn_id[r];
+  *ok = e >= 0 && e < a.n_env && i >= 0 && i < a.n_agent && t >= 0 && t < a.n_turn;
+  return (static_cast<int64_t>(e) * a.n_agent + i) * a.n_turn + t;
+}
+
+__global__ __launch_bounds__(256) void k_ga_hist(GaArgs a, int32_t* __restrict__ err,
+                                                 int32_t* __restrict__ hist) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= a.n_resp) return;
+  bool ok;
+  const int64_t key = key_of(a, r, &ok);
+  if (!ok) {
+    atomicOr(err, AT_GRPO_DATA_ID_RANGE);
+    return;
+  }
+  const float x = a.reward[r];
+  if (!(fabsf(x) <= 3.402823466e38f)) atomicOr(err, AT_GRPO_DATA_REWARD);
+  atomicAdd(&hist[key], 1);
+}
+
+// per-block sums of (key present, members) over 2048 keys
+__global__ __launch_bounds__(256) void k_ga_scan_partial(const int32_t* __restrict__ hist, int64_t n_keys,
+                                                         int32_t* __restrict__ bsum_p,
+                                                         int32_t* __restrict__ bsum_c) {
+  __shared__ int lds4[4];
+  const int64_t k0 = static_cast<int64_t>(blockIdx.x) * kKeysPerBlock + threadIdx.x * 8;
+  int p = 0, c = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int h = (k0 + e < n_keys) ? hist[k0 + e] : 0;
+    p += (h > 0);
+    c += h;
+  }
+  const int tp = block_sum_256_int(p, lds4);
+  const int tcn = block_sum_256_int(c, lds4);
+  if (threadIdx.x == 0) {
+    bsum_p[blockIdx.x] = tp;
+    bsum_c[blockIdx.x] = tcn;
+  }
+}
+
+// single block: exclusive scan of the block sums; totals -> n_groups and the closing CSR offset
+__global__ __launch_bounds__(256) void k_ga_scan_top(int64_t n_blocks, int32_t* __restrict__ bsum_p,
+                                                     int32_t* __restrict__ bsum_c,
+                                                     int32_t* __restrict__ n_groups,
+                                                     int32_t* __restrict__ seg_offsets) {
+  __shared__ int lds4[4];
+  int run_p = 0, run_c = 0;
+  for (int64_t base = 0; base < n_blocks; base += 256) {
+    const int64_t b = base + threadIdx.x;
+    const int vp = (b < n_blocks) ? bsum_p[b] : 0;
+    const int vc = (b < n_blocks) ? bsum_c[b] : 0;
+    int tp, tcn;
+    const int ep = block_exclusive_scan_256(vp, lds4, &tp);
+    const int ec = block_exclusive_scan_256(vc, lds4, &tcn);
+    if (b < n_blocks) {
+      bsum_p[b] = run_p + ep;
+      bsum_c[b] = run_c + ec;
+    }
+    run_p += tp;
+    run_c += tcn;
+  }
+  if (threadIdx.x == 0) {
+    *n_groups = run_p;
+    seg_offsets[run_p] = run_c;
+  }
+}
+
+// dense id of every present key, CSR offset and cleared cursor of every group
+__global__ __launch_bounds__(256) void k_ga_scan_apply(const int32_t* __restrict__ hist, int64_t n_keys,
+                                                       const int32_t* __restrict__ boff_p,
+                                                       const int32_t* __restrict__ boff_c,
+                                                       int32_t* __restrict__ gid_of_key,
+                                                       int32_t* __restrict__ seg_offsets,
+                                                       int32_t* __restrict__ cursor) {
+  __shared__ int lds4[4];
+  const int64_t k0 = static_cast<int64_t>(blockIdx.x) * kKeysPerBlock + threadIdx.x * 8;
+  int h[8];
+  int p = 0, c = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    h[e] = (k0 + e < n_keys) ? hist[k0 + e] : 0;
+    p += (h[e] > 0);
+    c += h[e];
+  }
+  int tp, tcn;
+  int gp = boff_p[blockIdx.x] + block_exclusive_scan_256(p, lds4, &tp);
+  int gc = boff_c[blockIdx.x] + block_exclusive_scan_256(c, lds4, &tcn);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    if (h[e] > 0) {
+      gid_of_key[k0 + e] = gp;
+      seg_offsets[gp] = gc;
+      cursor[gp] = 0;
+      ++gp;
+      gc += h[e];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void k_ga_scatter(GaArgs a, const int32_t* __restrict__ gid_of_key,
+                                                    const int32_t* __restrict__ seg_offsets,
+                                                    int32_t* __restrict__ cursor,
+                                                    int32_t* __restrict__ group_id,
+                                                    int32_t* __restrict__ arrival,
+                                                    float* __restrict__ adv) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= a.n_resp) return;
+  bool ok;
+  const int64_t key = key_of(a, r, &ok);
+  if (!ok) {
+    group_id[r] = -1;
+    adv[r] = 0.f;
+    return;
+  }
+  const int g = gid_of_key[key];
+  group_id[r] = g;
+  const int pos = seg_offsets[g] + atomicAdd(&cursor[g], 1);
+  arrival[pos] = r;
+}
+
+struct GaStat {
+  float eps_std;
+  int ddof, norm;
+};
+
+// Eq. (1) for one group, sequential in perm order (fp32, two passes).
+__device__ __forceinline__ void group_stats_seq(const int32_t* perm_seg, int n,
+                                                const float* __restrict__ reward, const GaStat& st,
+                                                float* __restrict__ adv, float* mean_out, float* std_out) {
+  const float x0 = reward[perm_seg[0]];
+  float sum = 0.f;
+  bool same = true;
+  for (int j = 0; j < n; ++j) {
+    const float x = reward[perm_seg[j]];
+    sum += x;
+    same = same && (x == x0);
+  }
+  if (same) {
+    for (int j = 0; j < n; ++j) adv[perm_seg[j]] = 0.f;
+    *mean_out = x0;
+    *std_out = 0.f;
+    return;
+  }
+  const float mean = sum / static_cast<float>(n);
+  float ss = 0.f;
+  for (int j = 0; j < n; ++j) {
+    const float d = reward[perm_seg[j]] - mean;
+    ss += d * d;
+  }
+  const int denom = n - st.ddof;
+  const float sd = denom > 0 ? sqrtf(ss / static_cast<float>(denom)) : 0.f;
+  for (int j = 0; j < n; ++j) {
+    const int r = perm_seg[j];
+    adv[r] = (st.norm == AT_GRPO_NORM_STD) ? (reward[r] - mean) / (sd + st.eps_std) : (reward[r] - mean);
+  }
+  *mean_out = mean;
+  *std_out = sd;
+}
+
+// groups of at most kSmallGroup members: one thread per group
+__global__ __launch_bounds__(256) void k_ga_finish_small(const int32_t* __restrict__ n_groups,
+                                                         const int32_t* __restrict__ seg_offsets,
+                                                         const int32_t* __restrict__ arrival,
+                                                         const float* __restrict__ reward, GaStat st,
+                                                         int32_t* perm, float* __restrict__ adv,
+                                                         float* __restrict__ group_mean,
+                                                         float* __restrict__ group_std) {
+  const int G = *n_groups;
+  const int stride = gridDim.x * 256;
+  for (int g = blockIdx.x * 256 + threadIdx.x; g < G; g += stride) {
+    const int off = seg_offsets[g], n = seg_offsets[g + 1] - off;
+    if (n > kSmallGroup) continue;
+    for (int j = 0; j < n; ++j) {
+      const int rj = arrival[off + j];
+      int rank = 0;
+      for (int i = 0; i < n; ++i) rank += (arrival[off + i] < rj);
+      perm[off + rank] = rj;
+    }
+    // perm[off .. off+n) was written by this thread only
+    float mu, sd;
+    group_stats_seq(perm + off, n, reward, st, adv, &mu, &sd);
+    if (group_mean) group_mean[g] = mu;
+    if (group_std) group_std[g] = sd;
+  }
+}
+
+// larger groups: one wavefront per group; ranks by counting, statistics by lane 0 in perm order
+__global__ __launch_bounds__(256) void k_ga_finish_large(const int32_t* __restrict__ n_groups,
+                                                         const int32_t* __restrict__ seg_offsets,
+                                                         const int32_t* __restrict__ arrival,
+                                                         const float* __restrict__ reward, GaStat st,
+                                                         int32_t* perm, float* __restrict__ adv,
+                                                         float* __restrict__ group_mean,
+                                                         float* __restrict__ group_std) {
+  const int G = *n_groups;
+  const int lane = threadIdx.x & 63;
+  const int wave = (blockIdx.x * 256 + threadIdx.x) >> 6;
+  const int n_waves = (gridDim.x * 256) >> 6;
+  for (int g = wave; g < G; g += n_waves) {
+    const int off = seg_offsets[g], n = seg_offsets[g + 1] - off;
+    if (n <= kSmallGroup) continue;
+    for (int j = lane; j < n; j += 64) {
+      const int rj = arrival[off + j];
+      int rank = 0;
+      for (int i = 0; i < n; ++i) rank += (arrival[off + i] < rj);
+      perm[off + rank] = rj;
+    }
+    __threadfence();   // the ranks below are read back by other lanes of this wavefront
+    // statistics: lane-strided partial sums combined in a fixed order
+    const float x0 = reward[perm[off]];
+    float sum = 0.f;
+    int same = 1;
+    for (int j = lane; j < n; j += 64) {
+      const float x = reward[perm[off + j]];
+      sum += x;
+      same &= (x == x0);
+    }
+    sum = wave_sum(sum);
+    sum = __shfl(sum, 0, 64);
+    same = __builtin_amdgcn_ballot_w64(same == 0) == 0ull;
+    float mean = sum / static_cast<float>(n), sd = 0.f;
+    if (same) {
+      for (int j = lane; j < n; j += 64) adv[perm[off + j]] = 0.f;
+      mean = x0;
+    } else {
+      float ss = 0.f;
+      for (int j = lane; j < n; j += 64) {
+        const float d = reward[perm[off + j]] - mean;
+        ss += d * d;
+      }
+      ss = wave_sum(ss);
+      ss = __shfl(ss, 0, 64);
+      const int denom = n - st.ddof;
+      sd = denom > 0 ? sqrtf(ss / static_cast<float>(denom)) : 0.f;
+      for (int j = lane; j < n; j += 64) {
+        const int r = perm[off + j];
+        adv[r] = (st.norm == AT_GRPO_NORM_STD) ? (reward[r] - mean) / (sd + st.eps_std) : (reward[r] - mean);
+      }
+    }
+    if (lane == 0) {
+      if (group_mean) group_mean[g] = mean;
+      if (group_std) group_std[g] = sd;
+    }
+  }
+}
+
+__global__ void k_ga_clear(int32_t* __restrict__ p, int64_t n) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0;
+}
+
+struct GaPlan {
+  int64_t n_keys, n_blocks;
+  int32_t *err, *hist, *gid_of_key, *cursor, *arrival, *bsum_p, *bsum_c;
+};
+
+bool plan(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn, WsAlloc& ws, GaPlan* p) {
+  if (n_resp <= 0 || n_env <= 0 || n_agent <= 0 || n_turn <= 0) return false;
+  const int64_t n_keys = static_cast<int64_t>(n_env) * n_agent * n_turn;
+  if (n_keys > (int64_t{1} << 28)) return false;
+  p->n_keys = n_keys;
+  p->n_blocks = ceil_div(n_keys, kKeysPerBlock);
+  p->err = ws.take<int32_t>(64);
+  p->hist = ws.take<int32_t>(static_cast<size_t>(n_keys));
+  p->gid_of_key = ws.take<int32_t>(static_cast<size_t>(n_keys));
+  p->cursor = ws.take<int32_t>(static_cast<size_t>(n_resp < n_keys ? n_resp : n_keys) + 1);
+  p->arrival = ws.take<int32_t>(static_cast<size_t>(n_resp));
+  p->bsum_p = ws.take<int32_t>(static_cast<size_t>(p->n_blocks));
+  p->bsum_c = ws.take<int32_t>(static_cast<size_t>(p->n_blocks));
+  return true;
+}
+
+}  // namespace
+
+size_t group_advantage_workspace(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn) {
+  WsAlloc ws(nullptr);
+  GaPlan p;
+  if (!plan(n_resp, n_env, n_agent, n_turn, ws, &p)) return 0;
+  return ws.bytes();
+}
+
+}  // namespace atg
+
+using namespace atg;
+
+extern "C" int at_grpo_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn,
+                                       const int32_t* env_id, const int32_t* agent_id,
+                                       const int32_t* turn_id, const float* reward, float eps_std,
+                                       int32_t ddof, int32_t norm, int32_t* group_id, int32_t* n_groups,
+                                       int32_t* seg_offsets, int32_t* perm, float* adv, float* group_mean,
+                                       float* group_std, void* workspace, size_t workspace_bytes,
+                                       void* hip_stream) {
+  if (!env_id || !agent_id || !turn_id || !reward || !group_id || !n_groups || !seg_offsets || !perm || !adv)
+    return AT_GRPO_EINVAL;
+  if (n_resp <= 0 || n_env <= 0 || n_agent <= 0 || n_turn <= 0) return AT_GRPO_EINVAL;
+  if (ddof != 0 && ddof != 1) return AT_GRPO_EINVAL;
+  if (norm != AT_GRPO_NORM_STD && norm != AT_GRPO_NORM_NONE) return AT_GRPO_EINVAL;
+  if (!(eps_std >= 0.f)) return AT_GRPO_EINVAL;
+  WsAlloc ws(workspace);
+  GaPlan p;
+  if (!plan(n_resp, n_env, n_agent, n_turn, ws, &p)) return AT_GRPO_EUNSUPPORTED;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < ws.bytes())
+    return AT_GRPO_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  ProfScope ps(PROF_GROUP, s);
+
+  const GaArgs a{n_resp, n_env, n_agent, n_turn, env_id, agent_id, turn_id, reward};
+  const GaStat st{eps_std, ddof, norm};
+  const unsigned rb = static_cast<unsigned>(ceil_div(n_resp, 256));
+  const unsigned kb = static_cast<unsigned>(p.n_blocks);
+
+  // err word and histogram are contiguous in the plan only by accident; clear them separately
+  hipLaunchKernelGGL(k_ga_clear, dim3(1), dim3(64), 0, s, p.err, int64_t{64});
+  ATG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_ga_clear, dim3(static_cast<unsigned>(ceil_div(p.n_keys, 1024) > 4096 ? 4096 : ceil_div(p.n_keys, 1024))),
+                     dim3(256), 0, s, p.hist, p.n_keys);
+  ATG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_ga_hist, dim3(rb), dim3(256), 0, s, a, p.err, p.hist);
+  ATG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_ga_scan_partial, dim3(kb), dim3(256), 0, s, p.hist, p.n_keys, p.bsum_p, p.bsum_c);
+  ATG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_ga_scan_top, dim3(1), dim3(256), 0, s, p.n_blocks, p.bsum_p, p.bsum_c, n_groups,
+                     seg_offsets);
+  ATG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_ga_scan_apply, dim3(kb), dim3(256), 0, s, p.hist, p.n_keys, p.bsum_p, p.bsum_c,
+                     p.gid_of_key, seg_offsets, p.cursor);
+  ATG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_ga_scatter, dim3(rb), dim3(256), 0, s, a, p.gid_of_key, seg_offsets, p.cursor,
+                     group_id, p.arrival, adv);
+  ATG_LAUNCH_CHECK();
+  // at most min(R, keys) groups exist; both finishing kernels stride over them
+  const int64_t g_max = n_resp < p.n_keys ? n_resp : p.n_keys;
+  const unsigned fs = static_cast<unsigned>(ceil_div(g_max, 256) > 4096 ? 4096 : ceil_div(g_max, 256));
+  const unsigned fl = static_cast<unsigned>(ceil_div(g_max, 4) > 4096 ? 4096 : ceil_div(g_max, 4));
+  hipLaunchKernelGGL(k_ga_finish_small, dim3(fs), dim3(256), 0, s, n_groups, seg_offsets, p.arrival, reward,
+                     st, perm, adv, group_mean, group_std);
+  ATG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_ga_finish_large, dim3(fl), dim3(256), 0, s, n_groups, seg_offsets, p.arrival, reward,
+                     st, perm, adv, group_mean, group_std);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}

@@ -1,0 +1,550 @@
+// LM-head kernels of the AT-GRPO policy loss (gfx950).
+//
+// Forward (log pi_theta(y_t) inside the ratio of Eq. 2): logits tiles z[v, t] = <W[v], hidden[t]>
+// are produced in MFMA accumulators, reduced to per-(vocab half-tile, token) (max, sum-exp)
+// partials and the target logit, and discarded.  A small combine kernel turns the partials into
+// lse and logp.
+//
+// Backward: logits tiles are recomputed, turned into dZ = g (onehot - softmax) in registers and
+// written once in the element type of the inputs, in both orientations; two further
+// contractions give dHidden = dZ W and dW = dZ^T hidden.
+#include "gemm_core.hpp"
+#include "head_kernels.hpp"
+
+namespace atg {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ int chunk_count(const int32_t* cnt, int c0, int TC) {
+  const int n = *cnt - c0;
+  return n < 0 ? 0 : (n > TC ? TC : n);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ------------------------------------------------------------------------------------------------
+// forward: A = W rows (vocab -> accumulator registers), B = hidden rows (tokens -> lanes)
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
+    const T* __restrict__ hidden, const T* __restrict__ W, const int32_t* __restrict__ idx,
+    const int32_t* __restrict__ cnt, int c0, const int32_t* __restrict__ token_id,
+    float* __restrict__ part_m, float* __restrict__ part_s, float* __restrict__ zy, int H, int V,
+    int TC, int n_vtiles) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int n = chunk_count(cnt, c0, TC);
+  if (n <= 0) return;
+  const TileOrder ord{n_vtiles, (n + kTile - 1) / kTile, 8};
+  const int total = ord.total();
+  const TileCoord tc;
+  const size_t row_bytes = static_cast<size_t>(H) * sizeof(T);
+  const int nk = static_cast<int>(row_bytes / kStepBytes);
+
+  for (int t = logical_workgroup(); t < total; t += gridDim.x) {
+    int vt, tt;
+    ord.decode(t, &vt, &tt);
+    const int v0 = vt * kTile, t0 = tt * kTile;
+
+    int tcol[4], ycol[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      tcol[j] = t0 + tc.b_row(j);
+      ycol[j] = (tcol[j] < n) ? token_id[idx[c0 + tcol[j]]] : -1;
+    }
+
+    floatx16 acc[4][4];
+    gemm_tile<T>(
+        acc,
+        [&](int row) {
+          const int v = min(v0 + row, V - 1);
+          return reinterpret_cast<const char*>(W) + static_cast<size_t>(v) * row_bytes;
+        },
+        [&](int row) {
+          const int tk = min(t0 + row, n - 1);
+          return reinterpret_cast<const char*>(hidden) + static_cast<size_t>(idx[c0 + tk]) * row_bytes;
+        },
+        nk, smem);
+
+    const int vbase = v0 + tc.wm * 128;        // first vocab row this wavefront holds
+    const int vrem = V - vbase;                // rows of it that exist (may be <= 0)
+    const bool ragged = vrem < 128;
+    const size_t prow = static_cast<size_t>(vt * 2 + tc.wm) * TC;
+
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float mx = -INFINITY;
+      if (!ragged) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[i][j][r]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int vl = i * 32 + 8 * (r >> 2) + 4 * tc.half + (r & 3);
+            if (vl < vrem) mx = fmaxf(mx, acc[i][j][r]);
+          }
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m2 = (mx == -INFINITY) ? 0.f : mx * kLog2e;
+      float sum = 0.f;
+      if (!ragged) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[i][j][r], kLog2e, -m2));
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int vl = i * 32 + 8 * (r >> 2) + 4 * tc.half + (r & 3);
+            if (vl < vrem) sum += fast_exp2(fmaf(acc[i][j][r], kLog2e, -m2));
+          }
+      }
+      sum += __shfl_xor(sum, 32, 64);
+      if (tc.half == 0 && tcol[j] < n) {
+        part_m[prow + tcol[j]] = (mx == -INFINITY) ? -INFINITY : m2;
+        part_s[prow + tcol[j]] = sum;
+      }
+      // target logit: held by exactly one lane of one wavefront of one tile
+      const int rel = ycol[j] - vbase;
+      const bool hit = (tcol[j] < n) && rel >= 0 && rel < 128 && (((rel >> 2) & 1) == tc.half);
+      if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
+        float zt = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int vl = i * 32 + 8 * (r >> 2) + (r & 3);   // half bit compared separately
+            if ((rel & ~4) == vl) zt = acc[i][j][r];
+          }
+        if (hit) zy[tcol[j]] = zt;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// combine: 256 threads = 64 tokens x 4 partial slices
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_lse_combine(const int32_t* __restrict__ idx,
+                                                     const int32_t* __restrict__ cnt, int c0, int TC,
+                                                     int n_part, const float* __restrict__ part_m,
+                                                     const float* __restrict__ part_s,
+                                                     const float* __restrict__ zy,
+                                                     float* __restrict__ logp, float* __restrict__ lse) {
+  __shared__ float sm[4][64], ss[4][64];
+  const int n = chunk_count(cnt, c0, TC);
+  const int tx = threadIdx.x & 63, py = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + tx;
+  if (blockIdx.x * 64 >= n) return;
+  float M = -INFINITY, S = 0.f;
+  if (j < n) {
+    for (int p = py; p < n_part; p += 4) {
+      const float m = part_m[static_cast<size_t>(p) * TC + j];
+      const float s = part_s[static_cast<size_t>(p) * TC + j];
+      if (m == -INFINITY) continue;
+      const float Mn = fmaxf(M, m);
+      S = S * fast_exp2(M - Mn) + s * fast_exp2(m - Mn);
+      M = Mn;
+    }
+  }
+  sm[py][tx] = M;
+  ss[py][tx] = S;
+  __syncthreads();
+  if (py == 0 && j < n) {
+    float Mt = fmaxf(fmaxf(sm[0][tx], sm[1][tx]), fmaxf(sm[2][tx], sm[3][tx]));
+    float St = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (sm[q][tx] != -INFINITY) St += ss[q][tx] * fast_exp2(sm[q][tx] - Mt);
+    const float l = (Mt + __log2f(St)) * kLn2;
+    const int row = idx[c0 + j];
+    logp[row] = zy[j] - l;
+    if (lse) lse[row] = l;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// transposes (64 x 64 tiles through LDS)
+// ------------------------------------------------------------------------------------------------
+// dst[c][r] = src_row(r)[c] for r < rows_valid, 0 for rows_valid <= r < rows_pad; c < cols.
+// src_row(r) = src + idx[c0 + r] * src_ld when idx != null, else src + r * src_ld.
+// When cnt != null, rows_valid = chunk count and rows_pad = that rounded up to 256.
+template <typename T>
+__global__ __launch_bounds__(256) void k_transpose(const T* __restrict__ src, int64_t src_ld,
+                                                   const int32_t* __restrict__ idx,
+                                                   const int32_t* __restrict__ cnt, int c0, int TC,
+                                                   int rows_valid, int rows_pad, int cols,
+                                                   T* __restrict__ dst, int64_t dst_ld) {
+  __shared__ T tile[64][65];
+  if (cnt) {
+    rows_valid = chunk_count(cnt, c0, TC);
+    rows_pad = (rows_valid + kTile - 1) / kTile * kTile;
+  }
+  const int r0 = blockIdx.x * 64, col0 = blockIdx.y * 64;
+  if (r0 >= rows_pad) return;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const int r = r0 + ty + 4 * k, c = col0 + tx;
+    T v{};
+    if (r < rows_valid && c < cols) {
+      const int64_t sr = idx ? static_cast<int64_t>(idx[c0 + r]) : static_cast<int64_t>(r);
+      v = src[sr * src_ld + c];
+    }
+    tile[ty + 4 * k][tx] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const int c = col0 + ty + 4 * k, r = r0 + tx;
+    if (c < cols && r < rows_pad) dst[static_cast<int64_t>(c) * dst_ld + r] = tile[tx][ty + 4 * k];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dZ: recompute logits, emit dZ[t][v] and dZt[v][t]
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+struct Pack4;
+template <>
+struct Pack4<float> {
+  static __device__ __forceinline__ void store(float* p, float a, float b, float c, float d) {
+    *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+  }
+};
+template <>
+struct Pack4<bf16_t> {
+  static __device__ __forceinline__ void store(bf16_t* p, float a, float b, float c, float d) {
+    uint2 u;
+    u.x = static_cast<uint32_t>(f32_to_bf16(a).bits) | (static_cast<uint32_t>(f32_to_bf16(b).bits) << 16);
+    u.y = static_cast<uint32_t>(f32_to_bf16(c).bits) | (static_cast<uint32_t>(f32_to_bf16(d).bits) << 16);
+    *reinterpret_cast<uint2*>(p) = u;
+  }
+};
+
+template <typename T>
+__global__ __launch_bounds__(kGemmThreads) void k_head_dz(
+    const T* __restrict__ hidden, const T* __restrict__ W, const int32_t* __restrict__ idx,
+    const int32_t* __restrict__ cnt, int c0, const int32_t* __restrict__ token_id,
+    const float* __restrict__ lse, const float* __restrict__ coef, T* __restrict__ dZ,
+    T* __restrict__ dZt, int H, int V, int Vp, int TC, int n_vtiles) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int n = chunk_count(cnt, c0, TC);
+  if (n <= 0) return;
+  const TileOrder ord{n_vtiles, (n + kTile - 1) / kTile, 8};
+  const int total = ord.total();
+  const TileCoord tc;
+  const size_t row_bytes = static_cast<size_t>(H) * sizeof(T);
+  const int nk = static_cast<int>(row_bytes / kStepBytes);
+
+  for (int t = logical_workgroup(); t < total; t += gridDim.x) {
+    int vt, tt;
+    ord.decode(t, &vt, &tt);
+    const int v0 = vt * kTile, t0 = tt * kTile;
+
+    int tcol[4], ycol[4];
+    float gcol[4], l2col[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      tcol[j] = t0 + tc.b_row(j);
+      if (tcol[j] < n) {
+        const int row = idx[c0 + tcol[j]];
+        ycol[j] = token_id[row];
+        gcol[j] = coef[row];
+        l2col[j] = lse[row] * kLog2e;
+      } else {
+        ycol[j] = -1;
+        gcol[j] = 0.f;
+        l2col[j] = 0.f;
+      }
+    }
+
+    floatx16 acc[4][4];
+    gemm_tile<T>(
+        acc,
+        [&](int row) {
+          const int v = min(v0 + row, V - 1);
+          return reinterpret_cast<const char*>(W) + static_cast<size_t>(v) * row_bytes;
+        },
+        [&](int row) {
+          const int tk = min(t0 + row, n - 1);
+          return reinterpret_cast<const char*>(hidden) + static_cast<size_t>(idx[c0 + tk]) * row_bytes;
+        },
+        nk, smem);
+
+    const int vbase = v0 + tc.wm * 128;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float g = gcol[j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int v = vbase + i * 32 + 8 * q + 4 * tc.half;   // first of 4 consecutive vocab rows
+          float d[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float p = fast_exp2(fmaf(acc[i][j][q * 4 + e], kLog2e, -l2col[j]));
+            float x = -g * p;
+            if (v + e == ycol[j]) x += g;
+            d[e] = (v + e < V && tcol[j] < n) ? x : 0.f;   // k padding and rows past the count are 0
+          }
+          if (v < Vp) Pack4<T>::store(dZ + static_cast<size_t>(tcol[j]) * Vp + v, d[0], d[1], d[2], d[3]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (v + e < V) dZt[static_cast<size_t>(v + e) * TC + tcol[j]] = from_f32<T>(d[e]);
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dHidden: A = dZ rows (tokens -> registers), B = Wt rows (h -> lanes), k = vocab
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kGemmThreads) void k_head_dh(const T* __restrict__ dZ,
+                                                          const T* __restrict__ Wt,
+                                                          const int32_t* __restrict__ idx,
+                                                          const int32_t* __restrict__ cnt, int c0,
+                                                          T* __restrict__ d_hidden, int H, int Vp,
+                                                          int TC) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int n = chunk_count(cnt, c0, TC);
+  if (n <= 0) return;
+  const TileOrder ord{(n + kTile - 1) / kTile, (H + kTile - 1) / kTile, 8};
+  const int total = ord.total();
+  const TileCoord tc;
+  const size_t row_bytes = static_cast<size_t>(Vp) * sizeof(T);
+  const int nk = static_cast<int>(row_bytes / kStepBytes);
+
+  for (int t = logical_workgroup(); t < total; t += gridDim.x) {
+    int tt, ht;
+    ord.decode(t, &tt, &ht);
+    const int t0 = tt * kTile, h0 = ht * kTile;
+    floatx16 acc[4][4];
+    gemm_tile<T>(
+        acc,
+        [&](int row) { return reinterpret_cast<const char*>(dZ) + static_cast<size_t>(t0 + row) * row_bytes; },
+        [&](int row) {
+          const int h = min(h0 + row, H - 1);
+          return reinterpret_cast<const char*>(Wt) + static_cast<size_t>(h) * row_bytes;
+        },
+        nk, smem);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = t0 + tc.a_row(i, r);
+        if (j >= n) continue;
+        T* out = d_hidden + static_cast<size_t>(idx[c0 + j]) * H;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const int h = h0 + tc.b_row(jj);
+          if (h < H) out[h] = from_f32<T>(acc[i][jj][r]);
+        }
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dW: A = dZt rows (vocab -> registers), B = hT rows (h -> lanes), k = tokens of the super-chunk
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kGemmThreads) void k_head_dw(const T* __restrict__ dZt,
+                                                          const T* __restrict__ hT,
+                                                          const int32_t* __restrict__ cnt, int c0,
+                                                          float* __restrict__ dW, int H, int V, int TC,
+                                                          int n_vtiles, int accumulate, int first_chunk) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int n = chunk_count(cnt, c0, TC);
+  if (n <= 0 && !(first_chunk && !accumulate)) return;
+  const TileOrder ord{n_vtiles, (H + kTile - 1) / kTile, 8};
+  const int total = ord.total();
+  const TileCoord tc;
+  const size_t row_bytes = static_cast<size_t>(TC) * sizeof(T);
+  const int k_tokens = (n + kTile - 1) / kTile * kTile;
+  const int nk = static_cast<int>(static_cast<size_t>(k_tokens) * sizeof(T) / kStepBytes);
+
+  for (int t = logical_workgroup(); t < total; t += gridDim.x) {
+    int vt, ht;
+    ord.decode(t, &vt, &ht);
+    const int v0 = vt * kTile, h0 = ht * kTile;
+    floatx16 acc[4][4];
+    gemm_tile<T>(
+        acc,
+        [&](int row) {
+          const int v = min(v0 + row, V - 1);
+          return reinterpret_cast<const char*>(dZt) + static_cast<size_t>(v) * row_bytes;
+        },
+        [&](int row) {
+          const int h = min(h0 + row, H - 1);
+          return reinterpret_cast<const char*>(hT) + static_cast<size_t>(h) * row_bytes;
+        },
+        nk, smem);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int v = v0 + tc.a_row(i, r);
+        if (v >= V) continue;
+        float* out = dW + static_cast<size_t>(v) * H;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const int h = h0 + tc.b_row(jj);
+          if (h < H) out[h] = accumulate ? out[h] + acc[i][jj][r] : acc[i][jj][r];
+        }
+      }
+  }
+}
+
+template <typename K>
+int allow_big_lds(K kernel) {
+  ATG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+  return AT_GRPO_OK;
+}
+
+int gemm_grid() {
+  int cus = device_cu_count();
+  if (cus <= 0) cus = 256;
+  return cus;
+}
+
+}  // namespace
+
+// ================================================================================================
+// launchers
+// ================================================================================================
+int launch_head_fwd(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
+                    const int32_t* token_id, float* part_m, float* part_s, float* zy, hipStream_t s) {
+  ProfScope ps(PROF_HEAD_FWD, s);
+  if (g.dtype == AT_GRPO_BF16) {
+    auto k = k_head_fwd<bf16_t>;
+    ATG_TRY(allow_big_lds(k));
+    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
+                       static_cast<const bf16_t*>(hidden), static_cast<const bf16_t*>(W), ch.idx, ch.cnt,
+                       ch.c0, token_id, part_m, part_s, zy, g.H, g.V, g.TC, g.n_vtiles);
+  } else {
+    auto k = k_head_fwd<float>;
+    ATG_TRY(allow_big_lds(k));
+    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
+                       static_cast<const float*>(hidden), static_cast<const float*>(W), ch.idx, ch.cnt,
+                       ch.c0, token_id, part_m, part_s, zy, g.H, g.V, g.TC, g.n_vtiles);
+  }
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_lse_combine(const HeadGeom& g, const HeadChunk& ch, const float* part_m, const float* part_s,
+                       const float* zy, float* logp, float* lse, hipStream_t s) {
+  ProfScope ps(PROF_LSE_COMBINE, s);
+  hipLaunchKernelGGL(k_lse_combine, dim3(g.TC / 64), dim3(256), 0, s, ch.idx, ch.cnt, ch.c0, g.TC,
+                     2 * g.n_vtiles, part_m, part_s, zy, logp, lse);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_transpose_w(const HeadGeom& g, const void* W, void* Wt, hipStream_t s) {
+  ProfScope ps(PROF_TRANSPOSE, s);
+  dim3 grid(static_cast<unsigned>(ceil_div(g.Vp, 64)), static_cast<unsigned>(ceil_div(g.H, 64)));
+  if (g.dtype == AT_GRPO_BF16)
+    hipLaunchKernelGGL(k_transpose<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t*>(W),
+                       static_cast<int64_t>(g.H), nullptr, nullptr, 0, 0, g.V, g.Vp, g.H,
+                       static_cast<bf16_t*>(Wt), static_cast<int64_t>(g.Vp));
+  else
+    hipLaunchKernelGGL(k_transpose<float>, grid, dim3(256), 0, s, static_cast<const float*>(W),
+                       static_cast<int64_t>(g.H), nullptr, nullptr, 0, 0, g.V, g.Vp, g.H,
+                       static_cast<float*>(Wt), static_cast<int64_t>(g.Vp));
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_gather_transpose_hidden(const HeadGeom& g, const HeadChunk& ch, const void* hidden, void* hT,
+                                   hipStream_t s) {
+  ProfScope ps(PROF_TRANSPOSE, s);
+  dim3 grid(static_cast<unsigned>(g.TC / 64), static_cast<unsigned>(ceil_div(g.H, 64)));
+  if (g.dtype == AT_GRPO_BF16)
+    hipLaunchKernelGGL(k_transpose<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t*>(hidden),
+                       static_cast<int64_t>(g.H), ch.idx, ch.cnt, ch.c0, g.TC, 0, 0, g.H,
+                       static_cast<bf16_t*>(hT), static_cast<int64_t>(g.TC));
+  else
+    hipLaunchKernelGGL(k_transpose<float>, grid, dim3(256), 0, s, static_cast<const float*>(hidden),
+                       static_cast<int64_t>(g.H), ch.idx, ch.cnt, ch.c0, g.TC, 0, 0, g.H,
+                       static_cast<float*>(hT), static_cast<int64_t>(g.TC));
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_head_dz(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
+                   const int32_t* token_id, const float* lse, const float* coef, void* dZ, void* dZt,
+                   hipStream_t s) {
+  ProfScope ps(PROF_HEAD_DZ, s);
+  if (g.dtype == AT_GRPO_BF16) {
+    auto k = k_head_dz<bf16_t>;
+    ATG_TRY(allow_big_lds(k));
+    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
+                       static_cast<const bf16_t*>(hidden), static_cast<const bf16_t*>(W), ch.idx, ch.cnt,
+                       ch.c0, token_id, lse, coef, static_cast<bf16_t*>(dZ), static_cast<bf16_t*>(dZt),
+                       g.H, g.V, g.Vp, g.TC, g.n_vtiles);
+  } else {
+    auto k = k_head_dz<float>;
+    ATG_TRY(allow_big_lds(k));
+    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
+                       static_cast<const float*>(hidden), static_cast<const float*>(W), ch.idx, ch.cnt,
+                       ch.c0, token_id, lse, coef, static_cast<float*>(dZ), static_cast<float*>(dZt), g.H,
+                       g.V, g.Vp, g.TC, g.n_vtiles);
+  }
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_head_dh(const HeadGeom& g, const HeadChunk& ch, const void* dZ, const void* Wt, void* d_hidden,
+                   hipStream_t s) {
+  ProfScope ps(PROF_HEAD_DH, s);
+  if (g.dtype == AT_GRPO_BF16) {
+    auto k = k_head_dh<bf16_t>;
+    ATG_TRY(allow_big_lds(k));
+    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
+                       static_cast<const bf16_t*>(dZ), static_cast<const bf16_t*>(Wt), ch.idx, ch.cnt, ch.c0,
+                       static_cast<bf16_t*>(d_hidden), g.H, g.Vp, g.TC);
+  } else {
+    auto k = k_head_dh<float>;
+    ATG_TRY(allow_big_lds(k));
+    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
+                       static_cast<const float*>(dZ), static_cast<const float*>(Wt), ch.idx, ch.cnt, ch.c0,
+                       static_cast<float*>(d_hidden), g.H, g.Vp, g.TC);
+  }
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_head_dw(const HeadGeom& g, const HeadChunk& ch, const void* dZt, const void* hT, float* dW,
+                   int accumulate, int first_chunk, hipStream_t s) {
+  ProfScope ps(PROF_HEAD_DW, s);
+  if (g.dtype == AT_GRPO_BF16) {
+    auto k = k_head_dw<bf16_t>;
+    ATG_TRY(allow_big_lds(k));
+    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
+                       static_cast<const bf16_t*>(dZt), static_cast<const bf16_t*>(hT), ch.cnt, ch.c0, dW,
+                       g.H, g.V, g.TC, g.n_vtiles, accumulate, first_chunk);
+  } else {
+    auto k = k_head_dw<float>;
+    ATG_TRY(allow_big_lds(k));
+    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
+                       static_cast<const float*>(dZt), static_cast<const float*>(hT), ch.cnt, ch.c0, dW, g.H,
+                       g.V, g.TC, g.n_vtiles, accumulate, first_chunk);
+  }
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+}  // namespace atg

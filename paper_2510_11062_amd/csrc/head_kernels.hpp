@@ -1,0 +1,57 @@
+// Launchers of the LM-head kernels: forward contraction with online-softmax partials, the
+// partial combine, and the three backward contractions.  All take device-side token counts, so
+// no launch depends on a host read-back.
+#pragma once
+
+#include "common.hpp"
+
+namespace atg {
+
+// Geometry of one head pass over a super-chunk of at most TC compacted tokens.
+struct HeadGeom {
+  int dtype;        // at_grpo_dtype
+  int H, V;
+  int Vp;           // V rounded up to 64 (k padding of the dZ / W^T buffers)
+  int TC;           // tokens per super-chunk (multiple of 256)
+  int n_vtiles;     // ceil(V / 256)
+  int esize;        // bytes per element of hidden / W / dZ
+};
+
+struct HeadChunk {
+  const int32_t* idx;   // compacted token rows of this head (device), whole list
+  const int32_t* cnt;   // number of entries in idx (device scalar)
+  int32_t c0;           // first list position of this super-chunk
+};
+
+// part_m / part_s: [2 * n_vtiles][TC] per-(vocab half-tile, token) running max (log2 domain) and
+// sum; zy: [TC] target logit.  hidden / W are the caller's tensors.
+int launch_head_fwd(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
+                    const int32_t* token_id, float* part_m, float* part_s, float* zy,
+                    hipStream_t s);
+
+// logp[row], lse[row] for the rows of this super-chunk (lse may be null).
+int launch_lse_combine(const HeadGeom& g, const HeadChunk& ch, const float* part_m,
+                       const float* part_s, const float* zy, float* logp, float* lse,
+                       hipStream_t s);
+
+// Wt[H][Vp] = W[V][H]^T, zero in the k padding.
+int launch_transpose_w(const HeadGeom& g, const void* W, void* Wt, hipStream_t s);
+
+// hT[H][TC] = (gathered hidden rows of this super-chunk)^T, zero for columns past the count.
+int launch_gather_transpose_hidden(const HeadGeom& g, const HeadChunk& ch, const void* hidden,
+                                   void* hT, hipStream_t s);
+
+// dZ[TC][Vp] and dZt[V][TC] for this super-chunk (element type of hidden).
+int launch_head_dz(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
+                   const int32_t* token_id, const float* lse, const float* coef, void* dZ, void* dZt,
+                   hipStream_t s);
+
+// d_hidden[row] = dZ[j] . Wt^T for the rows of this super-chunk.
+int launch_head_dh(const HeadGeom& g, const HeadChunk& ch, const void* dZ, const void* Wt,
+                   void* d_hidden, hipStream_t s);
+
+// dW[V][H] (+)= dZt . hT^T.  first_chunk: runs even for an empty list so that dW is defined.
+int launch_head_dw(const HeadGeom& g, const HeadChunk& ch, const void* dZt, const void* hT, float* dW,
+                   int accumulate, int first_chunk, hipStream_t s);
+
+}  // namespace atg

@@ -1,0 +1,377 @@
+// Per-token streaming kernels of the AT-GRPO policy loss (gfx950): routing rows to responses and
+// heads (the per-model batches B_m of Sec. 3), stable compaction, the clipped surrogate of
+// Eq. (2) with a fixed-order reduction, and the backward coefficient d loss / d logp.
+#include "token_kernels.hpp"
+
+namespace atg {
+
+namespace {
+
+__global__ void k_fill_i32(int32_t* __restrict__ p, int64_t n, int32_t value) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride)
+    p[i] = value;
+}
+
+__global__ void k_zero16(uint4* __restrict__ p, int64_t n16) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  const uint4 z = make_uint4(0, 0, 0, 0);
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride)
+    p[i] = z;
+}
+
+__device__ __forceinline__ int head_of_response(int r, int n_heads, int n_agent,
+                                                const int32_t* resp_agent,
+                                                const int32_t* head_of_agent, int32_t* err) {
+  if (n_heads == 1 || resp_agent == nullptr || head_of_agent == nullptr) return 0;
+  const int a = resp_agent[r];
+  if (a < 0 || a >= n_agent) {
+    atomicOr(err, AT_GRPO_DATA_AGENT_RANGE);
+    return -1;
+  }
+  const int h = head_of_agent[a];
+  if (h < 0 || h >= n_heads) {
+    atomicOr(err, AT_GRPO_DATA_AGENT_RANGE);
+    return -1;
+  }
+  return h;
+}
+
+// one wavefront per response
+__global__ __launch_bounds__(256) void k_route(TokenLayout L, int32_t* __restrict__ err,
+                                               int32_t* __restrict__ resp_of_tok,
+                                               int32_t* __restrict__ flag) {
+  const int lane = threadIdx.x & 63;
+  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int n_waves = (gridDim.x * blockDim.x) >> 6;
+  for (int r = wave; r < L.n_resp; r += n_waves) {
+    const int64_t lo = L.cu_seqlens[r], hi = L.cu_seqlens[r + 1];
+    if (lo < 0 || hi < lo || hi > L.n_tok) {
+      if (lane == 0) atomicOr(err, AT_GRPO_DATA_SEQLENS);
+      continue;
+    }
+    const int head = head_of_response(r, L.n_heads, L.n_agent, L.resp_agent, L.head_of_agent, err);
+    for (int64_t t = lo + lane; t < hi; t += 64) {
+      bool on = (head >= 0) && (L.mask == nullptr || L.mask[t] != 0);
+      if (on && L.token_id != nullptr) {
+        const int y = L.token_id[t];
+        if (y < 0 || y >= L.V) {
+          atomicOr(err, AT_GRPO_DATA_TOKEN_RANGE);
+          on = false;
+        }
+      }
+      resp_of_tok[t] = r;
+      flag[t] = on ? head : -1;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void k_count(const int32_t* __restrict__ flag, int64_t n_tok,
+                                               int n_heads, int64_t n_blk,
+                                               int32_t* __restrict__ blk_cnt) {
+  __shared__ int lds4[4];
+  const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kTokPerBlock + threadIdx.x * 8;
+  int f[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) f[e] = (t0 + e < n_tok) ? flag[t0 + e] : -1;
+  for (int m = 0; m < n_heads; ++m) {
+    int c = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c += (f[e] == m);
+    const int tot = block_sum_256_int(c, lds4);
+    if (threadIdx.x == 0) blk_cnt[m * n_blk + blockIdx.x] = tot;
+  }
+}
+
+// single block: exclusive scan of the per-block counts of every head
+__global__ __launch_bounds__(256) void k_scan_blocks(const int32_t* __restrict__ blk_cnt, int n_heads,
+                                                     int64_t n_blk, int32_t* __restrict__ blk_off,
+                                                     int32_t* __restrict__ cnt) {
+  __shared__ int lds4[4];
+  for (int m = 0; m < n_heads; ++m) {
+    int running = 0;
+    for (int64_t base = 0; base < n_blk; base += 256) {
+      const int64_t b = base + threadIdx.x;
+      const int v = (b < n_blk) ? blk_cnt[m * n_blk + b] : 0;
+      int tot;
+      const int ex = block_exclusive_scan_256(v, lds4, &tot);
+      if (b < n_blk) blk_off[m * n_blk + b] = running + ex;
+      running += tot;
+    }
+    if (threadIdx.x == 0) cnt[m] = running;
+  }
+  for (int m = n_heads + threadIdx.x; m < kMaxHeads; m += 256) cnt[m] = 0;
+}
+
+__global__ __launch_bounds__(256) void k_scatter(const int32_t* __restrict__ flag, int64_t n_tok,
+                                                 int n_heads, int64_t n_blk,
+                                                 const int32_t* __restrict__ blk_off,
+                                                 int32_t* __restrict__ idx) {
+  __shared__ int lds4[4];
+  const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kTokPerBlock + threadIdx.x * 8;
+  int f[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) f[e] = (t0 + e < n_tok) ? flag[t0 + e] : -1;
+  for (int m = 0; m < n_heads; ++m) {
+    int c = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c += (f[e] == m);
+    int tot;
+    int pos = blk_off[m * n_blk + blockIdx.x] + block_exclusive_scan_256(c, lds4, &tot);
+    int32_t* out = idx + static_cast<int64_t>(m) * n_tok;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (f[e] == m) out[pos++] = static_cast<int32_t>(t0 + e);
+  }
+}
+
+// one wavefront per response: participating rows of the response
+__global__ __launch_bounds__(256) void k_resp_len(TokenLayout L, const int32_t* __restrict__ flag,
+                                                  int32_t* __restrict__ resp_len) {
+  const int lane = threadIdx.x & 63;
+  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int n_waves = (gridDim.x * blockDim.x) >> 6;
+  for (int r = wave; r < L.n_resp; r += n_waves) {
+    const int64_t lo = L.cu_seqlens[r], hi = L.cu_seqlens[r + 1];
+    int c = 0;
+    if (!(lo < 0 || hi < lo || hi > L.n_tok))
+      for (int64_t t = lo + lane; t < hi; t += 64) c += (flag[t] >= 0);
+    c = wave_sum_int(c);
+    if (lane == 0) resp_len[r] = c;
+  }
+}
+
+// single block: responses with at least one participating row, per head
+__global__ __launch_bounds__(256) void k_resp_cnt(TokenLayout L, const int32_t* __restrict__ resp_len,
+                                                  int32_t* __restrict__ err,
+                                                  int32_t* __restrict__ resp_cnt) {
+  __shared__ int lds4[4];
+  for (int m = 0; m < L.n_heads; ++m) {
+    int c = 0;
+    for (int r = threadIdx.x; r < L.n_resp; r += 256)
+      if (resp_len[r] > 0 &&
+          head_of_response(r, L.n_heads, L.n_agent, L.resp_agent, L.head_of_agent, err) == m)
+        ++c;
+    const int tot = block_sum_256_int(c, lds4);
+    if (threadIdx.x == 0) resp_cnt[m] = tot;
+  }
+}
+
+struct ClipConst {
+  float lo, hi;          // log-space thresholds
+  float one_minus, one_plus;
+};
+
+// Per-token pieces of Eq. (2).  Returns l_t; sets *bits and *ratio.
+__device__ __forceinline__ float surrogate_term(float logp, float old_logp, float A, const ClipConst& c,
+                                                int* bits, float* ratio) {
+  const float d = logp - old_logp;
+  const float r = expf(d);
+  const bool low = d < c.lo, high = d > c.hi;
+  const bool zero = (high && A > 0.f) || (low && A < 0.f);
+  *bits = (low ? AT_GRPO_CLIP_LOW : 0) | (high ? AT_GRPO_CLIP_HIGH : 0) | (zero ? AT_GRPO_CLIP_ZERO_GRAD : 0);
+  *ratio = r;
+  return zero ? (high ? c.one_plus : c.one_minus) * A : r * A;
+}
+
+__global__ __launch_bounds__(256) void k_surrogate(int64_t n_tok, int n_heads,
+                                                   const int32_t* __restrict__ flag,
+                                                   const int32_t* __restrict__ resp_of_tok,
+                                                   const int32_t* __restrict__ resp_len,
+                                                   const float* __restrict__ logp,
+                                                   const float* __restrict__ old_logp,
+                                                   const float* __restrict__ adv, ClipConst cc, int agg,
+                                                   uint8_t* __restrict__ clip_mask, int64_t n_blk256,
+                                                   float* __restrict__ blk_loss) {
+  __shared__ float lds4[4];
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  int f = -1;
+  float term = 0.f;
+  if (t < n_tok) {
+    f = flag[t];
+    int bits = 0;
+    if (f >= 0) {
+      const int r = resp_of_tok[t];
+      float ratio;
+      term = surrogate_term(logp[t], old_logp[t], adv[r], cc, &bits, &ratio);
+      if (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN) term /= static_cast<float>(resp_len[r]);
+    }
+    if (clip_mask) clip_mask[t] = static_cast<uint8_t>(bits);
+  }
+  for (int m = 0; m < n_heads; ++m) {
+    const float tot = block_sum_256(f == m ? term : 0.f, lds4);
+    if (threadIdx.x == 0) blk_loss[m * n_blk256 + blockIdx.x] = tot;
+  }
+}
+
+// one block per head: fixed-order sum of the per-block partials
+__global__ __launch_bounds__(256) void k_loss_final(int64_t n_blk256, const float* __restrict__ blk_loss,
+                                                    const int32_t* __restrict__ cnt,
+                                                    const int32_t* __restrict__ resp_cnt, int agg,
+                                                    float* __restrict__ loss, int32_t* __restrict__ n_valid) {
+  __shared__ float lds4[4];
+  const int m = blockIdx.x;
+  float acc = 0.f;
+  for (int64_t b = threadIdx.x; b < n_blk256; b += 256) acc += blk_loss[m * n_blk256 + b];
+  const float tot = block_sum_256(acc, lds4);
+  if (threadIdx.x == 0) {
+    const int denom = (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN) ? resp_cnt[m] : cnt[m];
+    loss[m] = denom > 0 ? -tot / static_cast<float>(denom) : 0.f;
+    if (n_valid) n_valid[m] = cnt[m];
+  }
+}
+
+__global__ __launch_bounds__(256) void k_coef(int64_t n_tok, int32_t* __restrict__ flag,
+                                              const int32_t* __restrict__ resp_of_tok,
+                                              const int32_t* __restrict__ resp_len,
+                                              const int32_t* __restrict__ cnt,
+                                              const int32_t* __restrict__ resp_cnt,
+                                              const float* __restrict__ logp,
+                                              const float* __restrict__ old_logp,
+                                              const float* __restrict__ adv, ClipConst cc, int agg,
+                                              const float* __restrict__ grad_loss,
+                                              float* __restrict__ coef) {
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (t >= n_tok) return;
+  const int f = flag[t];
+  float g = 0.f;
+  if (f >= 0) {
+    const int r = resp_of_tok[t];
+    const float A = adv[r];
+    int bits;
+    float ratio;
+    surrogate_term(logp[t], old_logp[t], A, cc, &bits, &ratio);
+    float w;
+    if (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN)
+      w = 1.f / (static_cast<float>(resp_cnt[f]) * static_cast<float>(resp_len[r]));
+    else
+      w = 1.f / static_cast<float>(cnt[f]);
+    if (!(bits & AT_GRPO_CLIP_ZERO_GRAD)) g = -w * A * ratio * (grad_loss ? grad_loss[f] : 1.f);
+    if (g == 0.f) {
+      g = 0.f;          // also folds -0
+      flag[t] = -1;
+    }
+  }
+  coef[t] = g;
+}
+
+__global__ __launch_bounds__(256) void k_zero_nonparticipating(int64_t n_tok,
+                                                               const int32_t* __restrict__ flag,
+                                                               float* __restrict__ logp,
+                                                               float* __restrict__ lse) {
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (t >= n_tok) return;
+  if (flag[t] < 0) {
+    logp[t] = 0.f;
+    if (lse) lse[t] = 0.f;
+  }
+}
+
+ClipConst make_clip(float eps_low, float eps_high) {
+  ClipConst c;
+  c.lo = static_cast<float>(log1p(-static_cast<double>(eps_low)));
+  c.hi = static_cast<float>(log1p(static_cast<double>(eps_high)));
+  c.one_minus = 1.f - eps_low;
+  c.one_plus = 1.f + eps_high;
+  return c;
+}
+
+unsigned grid_for(int64_t n, int per_block, int64_t cap = 1 << 20) {
+  int64_t g = ceil_div(n, per_block);
+  if (g < 1) g = 1;
+  if (g > cap) g = cap;
+  return static_cast<unsigned>(g);
+}
+
+}  // namespace
+
+int launch_fill_i32(int32_t* p, int64_t n, int32_t value, hipStream_t s) {
+  if (n <= 0) return AT_GRPO_OK;
+  hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(n, 256, 4096)), dim3(256), 0, s, p, n, value);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_fill_bytes16(void* p, int64_t n_bytes, hipStream_t s) {
+  if (n_bytes <= 0) return AT_GRPO_OK;
+  ProfScope ps(PROF_FILL, s);
+  hipLaunchKernelGGL(k_zero16, dim3(grid_for(n_bytes / 16, 256, 8192)), dim3(256), 0, s,
+                     static_cast<uint4*>(p), n_bytes / 16);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_route(const TokenLayout& L, const TokenScratch& S, hipStream_t s) {
+  ProfScope ps(PROF_PREP, s);
+  ATG_TRY(launch_fill_i32(S.err, 1, 0, s));
+  ATG_TRY(launch_fill_i32(S.resp_of_tok, L.n_tok, -1, s));
+  ATG_TRY(launch_fill_i32(S.flag, L.n_tok, -1, s));
+  hipLaunchKernelGGL(k_route, dim3(grid_for(L.n_resp, 4, 4096)), dim3(256), 0, s, L, S.err,
+                     S.resp_of_tok, S.flag);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_compact(const TokenLayout& L, const TokenScratch& S, bool with_idx, hipStream_t s) {
+  ProfScope ps(PROF_PREP, s);
+  const unsigned nb = static_cast<unsigned>(S.n_blk);
+  hipLaunchKernelGGL(k_count, dim3(nb), dim3(256), 0, s, S.flag, L.n_tok, L.n_heads, S.n_blk, S.blk_cnt);
+  ATG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(256), 0, s, S.blk_cnt, L.n_heads, S.n_blk, S.blk_off,
+                     S.cnt);
+  ATG_LAUNCH_CHECK();
+  if (with_idx) {
+    hipLaunchKernelGGL(k_scatter, dim3(nb), dim3(256), 0, s, S.flag, L.n_tok, L.n_heads, S.n_blk,
+                       S.blk_off, S.idx);
+    ATG_LAUNCH_CHECK();
+  }
+  return AT_GRPO_OK;
+}
+
+int launch_resp_len(const TokenLayout& L, const TokenScratch& S, hipStream_t s) {
+  ProfScope ps(PROF_PREP, s);
+  hipLaunchKernelGGL(k_resp_len, dim3(grid_for(L.n_resp, 4, 4096)), dim3(256), 0, s, L, S.flag,
+                     S.resp_len);
+  ATG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_resp_cnt, dim3(1), dim3(256), 0, s, L, S.resp_len, S.err, S.resp_cnt);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_surrogate(const TokenLayout& L, const TokenScratch& S, const float* logp, const float* old_logp,
+                     const float* adv, float eps_low, float eps_high, int agg, float* loss,
+                     uint8_t* clip_mask, int32_t* n_valid, hipStream_t s) {
+  ProfScope ps(PROF_SURROGATE, s);
+  const ClipConst cc = make_clip(eps_low, eps_high);
+  hipLaunchKernelGGL(k_surrogate, dim3(static_cast<unsigned>(S.n_blk256)), dim3(256), 0, s, L.n_tok,
+                     L.n_heads, S.flag, S.resp_of_tok, S.resp_len, logp, old_logp, adv, cc, agg, clip_mask,
+                     S.n_blk256, S.blk_loss);
+  ATG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_loss_final, dim3(L.n_heads), dim3(256), 0, s, S.n_blk256, S.blk_loss, S.cnt,
+                     S.resp_cnt, agg, loss, n_valid);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_coef(const TokenLayout& L, const TokenScratch& S, const float* logp, const float* old_logp,
+                const float* adv, float eps_low, float eps_high, int agg, const float* grad_loss,
+                float* coef, hipStream_t s) {
+  ProfScope ps(PROF_COEF, s);
+  const ClipConst cc = make_clip(eps_low, eps_high);
+  hipLaunchKernelGGL(k_coef, dim3(static_cast<unsigned>(S.n_blk256)), dim3(256), 0, s, L.n_tok, S.flag,
+                     S.resp_of_tok, S.resp_len, S.cnt, S.resp_cnt, logp, old_logp, adv, cc, agg, grad_loss,
+                     coef);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_zero_nonparticipating(const TokenLayout& L, const TokenScratch& S, float* logp, float* lse,
+                                 hipStream_t s) {
+  ProfScope ps(PROF_PREP, s);
+  hipLaunchKernelGGL(k_zero_nonparticipating, dim3(static_cast<unsigned>(S.n_blk256)), dim3(256), 0, s,
+                     L.n_tok, S.flag, logp, lse);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+}  // namespace atg

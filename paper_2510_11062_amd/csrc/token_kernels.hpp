@@ -1,0 +1,63 @@
+// Launchers of the per-token streaming kernels: routing of rows to responses and heads, validity
+// flags, stable per-head compaction, the clipped surrogate with its deterministic reduction, and
+// the backward coefficient.
+#pragma once
+
+#include "common.hpp"
+
+namespace atg {
+
+constexpr int kTokPerBlock = 2048;   // tokens handled by one 256-thread block (8 per thread)
+
+struct TokenLayout {
+  int64_t n_tok;
+  int32_t n_resp, n_heads, n_agent, V;
+  const int64_t* cu_seqlens;
+  const int32_t* token_id;
+  const uint8_t* mask;
+  const int32_t* resp_agent;
+  const int32_t* head_of_agent;
+};
+
+struct TokenScratch {
+  int32_t* err;          // [1] device error word
+  int32_t* resp_of_tok;  // [n_tok]
+  int32_t* flag;         // [n_tok] head of a participating row, -1 otherwise
+  int32_t* blk_cnt;      // [n_heads * n_blk]
+  int32_t* blk_off;      // [n_heads * n_blk]
+  int32_t* cnt;          // [kMaxHeads] participating rows per head
+  int32_t* idx;          // [n_heads * n_tok] compacted rows per head
+  int32_t* resp_len;     // [n_resp] participating rows per response
+  int32_t* resp_cnt;     // [kMaxHeads] responses with at least one participating row, per head
+  float* blk_loss;       // [n_heads * n_blk256] per-block partial sums of the surrogate
+  int64_t n_blk;         // ceil(n_tok / kTokPerBlock)
+  int64_t n_blk256;      // ceil(n_tok / 256)
+};
+
+int launch_fill_i32(int32_t* p, int64_t n, int32_t value, hipStream_t s);
+int launch_fill_bytes16(void* p, int64_t n_bytes, hipStream_t s);   // zero fill, n_bytes % 16 == 0
+
+// resp_of_tok, flag (participation by mask / token range / routing), error word checks.
+int launch_route(const TokenLayout& L, const TokenScratch& S, hipStream_t s);
+
+// cnt[m] and, when with_idx, the stable compaction idx[m * n_tok + ...] of rows with flag == m.
+int launch_compact(const TokenLayout& L, const TokenScratch& S, bool with_idx, hipStream_t s);
+
+// resp_len / resp_cnt (only needed for the sequence-mean aggregation).
+int launch_resp_len(const TokenLayout& L, const TokenScratch& S, hipStream_t s);
+
+// Per-token surrogate terms + clip mask + per-head loss (Eq. 2).  Needs route + compact(cnt).
+int launch_surrogate(const TokenLayout& L, const TokenScratch& S, const float* logp,
+                     const float* old_logp, const float* adv, float eps_low, float eps_high, int agg,
+                     float* loss, uint8_t* clip_mask, int32_t* n_valid, hipStream_t s);
+
+// Backward coefficient coef[t] = d loss / d logp_t; rewrites flag to -1 where coef == 0.
+int launch_coef(const TokenLayout& L, const TokenScratch& S, const float* logp, const float* old_logp,
+                const float* adv, float eps_low, float eps_high, int agg, const float* grad_loss,
+                float* coef, hipStream_t s);
+
+// logp = lse = 0 on rows with flag < 0.
+int launch_zero_nonparticipating(const TokenLayout& L, const TokenScratch& S, float* logp, float* lse,
+                                 hipStream_t s);
+
+}  // namespace atg

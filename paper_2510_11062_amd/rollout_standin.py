@@ -1,0 +1,35 @@
+"""Stand-in for the rollout engine at sizes the CPU oracle cannot cover.
+
+In the paper's system the sampled tokens and the behaviour-policy log-probs (pi_theta_old in
+Eq. 2) come from a separate inference engine, not from the training step.  For synthetic
+workloads this module plays that engine with stock torch ops: it draws y_t from softmax(h_t W^T)
+by inverse CDF and returns old_logp = log pi(y_t) + drift.  It is input generation only: the
+library never calls it, and nothing here is used to check the library's results.
+"""
+from __future__ import annotations
+
+import torch
+
+
+@torch.no_grad()
+def draw_tokens_and_old_logp(hidden, W_list, head_of_tok, valid, u, noise, rows_per_chunk: int = 4096):
+    """hidden [n, H]; W_list of [V, H]; head_of_tok int64 [n]; valid bool [n]; u float64 [n] in
+    [0, 1); noise float32 [n].  Returns (token_id int32 [n], old_logp float32 [n]); rows that are
+    not valid get token 0 and old_logp 0."""
+    n = hidden.shape[0]
+    dev = hidden.device
+    token_id = torch.zeros(n, dtype=torch.int32, device=dev)
+    old_logp = torch.zeros(n, dtype=torch.float32, device=dev)
+    for k, W in enumerate(W_list):
+        rows = torch.nonzero(valid & (head_of_tok == k)).squeeze(1)
+        Wf = W.float()
+        for s in range(0, rows.numel(), rows_per_chunk):
+            r = rows[s:s + rows_per_chunk]
+            logits = hidden[r].float() @ Wf.T
+            logp = torch.log_softmax(logits, dim=1)
+            cdf = torch.cumsum(torch.exp(logp), dim=1)
+            y = torch.searchsorted(cdf, u[r].float().unsqueeze(1)).squeeze(1).clamp_(max=W.shape[0] - 1)
+            token_id[r] = y.to(torch.int32)
+            old_logp[r] = logp.gather(1, y.unsqueeze(1)).squeeze(1) + noise[r]
+        del Wf
+    return token_id, old_logp

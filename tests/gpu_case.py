@@ -1,0 +1,43 @@
+"""Moves a host-side test case onto the GPU and drives the library through its Python binding."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2510_11062_amd import api
+
+
+class DeviceCase:
+    def __init__(self, c, device, token_id=None, old_logp=None, adv=None):
+        st, cfg = c.st, c.cfg
+        self.c = c
+        self.dev = device
+        i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
+        self.env_id, self.agent_id, self.turn_id = i32(st.env_id), i32(st.agent_id), i32(st.turn_id)
+        self.reward = torch.from_numpy(st.reward).to(device)
+        self.hidden = c.hidden_t.to(device)
+        self.W = [w.to(device) for w in c.W_t]
+        self.cu = torch.from_numpy(st.cu_seqlens).to(device)
+        self.mask = None if st.mask is None else torch.from_numpy(st.mask).to(device)
+        self.token_id = i32(c.token_id if token_id is None else token_id)
+        self.old_logp = torch.from_numpy(np.asarray(c.old_logp if old_logp is None else old_logp,
+                                                    dtype=np.float32)).to(device)
+        self.adv = torch.from_numpy(np.asarray(c.adv if adv is None else adv, dtype=np.float32)).to(device)
+        multi = cfg.n_heads > 1
+        self.resp_agent = i32(st.agent_id) if multi else None
+        self.head_of_agent = i32(st.head_of_agent) if multi else None
+
+    def batch(self):
+        return api.Batch(self.hidden, self.W, self.token_id, self.cu, self.mask, self.resp_agent,
+                         self.head_of_agent)
+
+    def layout_only(self):
+        return api.Batch(None, None, self.token_id, self.cu, self.mask, self.resp_agent, self.head_of_agent,
+                         n_tok=self.c.st.n_tok, V=self.c.cfg.V, n_heads=self.c.cfg.n_heads)
+
+
+def host(t):
+    t = t.detach().cpu()
+    if t.dtype == torch.bfloat16:
+        t = t.float()
+    return t.numpy()
