@@ -142,7 +142,7 @@ void make_plan(const at_grpo_batch* b, int call, WsAlloc& ws, Plan* p) {
   p->n_chunks = static_cast<int>(ceil_div(n_tok, tc));
 
   if (call == AT_GRPO_CALL_TOKEN_LOGPROB || call == AT_GRPO_CALL_POLICY_LOSS_FWD) {
-    const size_t np = static_cast<size_t>(2 * g.n_vtiles) * static_cast<size_t>(g.TC);
+    const size_t np = static_cast<size_t>(g.n_vtiles) * static_cast<size_t>(g.TC);
     p->part_m = ws.take<float>(np);
     p->part_s = ws.take<float>(np);
     p->zy = ws.take<float>(static_cast<size_t>(g.TC));

@@ -1,17 +1,23 @@
 // Workgroup-tile contraction on the gfx950 matrix cores.
 //
-// One 256-thread workgroup (4 wavefronts, 2 x 2) produces a 256 x 256 fp32 tile
+// One 512-thread workgroup (8 wavefronts, 4 x 2, two per SIMD) produces a 256 x 256 fp32 tile
 //   C[a, b] = sum_k A[a, k] * B[b, k]
 // from two operands that are both contiguous along k ("NT" layout).  Each wavefront owns a
-// 128 x 128 sub-tile held as 4 x 4 MFMA 32x32 accumulator blocks (256 accumulator registers per
-// lane).  k is consumed in steps of 128 bytes per row (64 bf16 or 32 fp32 elements): the step's
-// 256 + 256 row segments are staged through LDS, double buffered, with an XOR swizzle of the
-// 16-byte chunk index so that both the staging stores and the ds_read_b128 fragment loads are
-// free of bank conflicts.
+// 64 x 128 sub-tile held as 2 x 4 MFMA 32x32 accumulator blocks (128 accumulator registers per
+// lane).  k is consumed in steps of 128 bytes per row (64 bf16 or 32 fp32 elements).
+//
+// Data path: global -> LDS with direct-to-LDS loads (global_load_lds_dwordx4, 16 bytes per lane,
+// one instruction fills 8 rows x 128 bytes), two LDS stages, loads issued one full k-step ahead;
+// LDS -> registers with ds_read_b128, fragments fetched one 16-wide sub-step ahead of the MFMAs
+// that consume them.  The 16-byte chunk index of every row is XOR-swizzled (applied on the global
+// side of the direct loads, since their LDS side is fixed to lane * 16) so that the fragment reads
+// are free of bank conflicts.  The direct loads are issued through inline asm: the compiler would
+// otherwise make every later LDS read wait for all outstanding direct loads.  Their completion is
+// enforced by hand with s_waitcnt vmcnt(0) in front of the one workgroup barrier per k-step.
 //
 // Accumulator layout (per lane, block (i, j), register r = 0..15):
-//   a = wm*128 + i*32 + 8*(r/4) + 4*(lane/32) + (r%4)        (A row inside the tile)
-//   b = wn*128 + j*32 + lane%32                               (B row inside the tile)
+//   a = wm*64 + i*32 + 8*(r/4) + 4*(lane/32) + (r%4)        (A row inside the tile)
+//   b = wn*128 + j*32 + lane%32                              (B row inside the tile)
 #pragma once
 
 #include "common.hpp"
@@ -23,12 +29,17 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
 constexpr int kTile = 256;                       // rows of each operand per tile
 constexpr int kStepBytes = 128;                  // bytes of k per row per step
-constexpr int kGemmThreads = 256;
+constexpr int kWavesA = 4, kWavesB = 2;
+constexpr int kGemmThreads = kWavesA * kWavesB * 64;
+constexpr int kIB = kTile / kWavesA / 32;        // 2 accumulator block rows per wavefront
+constexpr int kJB = kTile / kWavesB / 32;        // 4 accumulator block columns per wavefront
 constexpr int kLdsOperand = kTile * kStepBytes;  // 32 KiB
 constexpr int kLdsStage = 2 * kLdsOperand;       // A then B
 constexpr int kLdsBytes = 2 * kLdsStage;         // two stages: 128 KiB
+constexpr int kRowsPerWave = kTile / (kWavesA * kWavesB);   // operand rows each wavefront loads
+constexpr int kLoadsPerWave = kRowsPerWave / 8;             // direct-load instructions per operand
 
-__device__ __forceinline__ int swz16(int row) { return ((row ^ (row >> 3)) & 7) << 4; }
+__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
 template <typename T>
 struct Mma;
@@ -58,111 +69,131 @@ struct TileCoord {
   __device__ __forceinline__ TileCoord() {
     lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    wm = wave >> 1;
-    wn = wave & 1;
+    wm = wave / kWavesB;
+    wn = wave % kWavesB;
     half = lane >> 5;
   }
   // A row (inside the tile) of accumulator register r of block row i
   __device__ __forceinline__ int a_row(int i, int r) const {
-    return wm * 128 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+    return wm * (kTile / kWavesA) + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
   }
   // B row (inside the tile) of block column j
-  __device__ __forceinline__ int b_row(int j) const { return wn * 128 + j * 32 + (lane & 31); }
+  __device__ __forceinline__ int b_row(int j) const { return wn * (kTile / kWavesB) + j * 32 + (lane & 31); }
 };
+
+// 16 bytes per lane, global -> LDS at (wave-uniform) lds_addr + lane * 16.
+__device__ __forceinline__ void direct_load16(const char* g, uint32_t lds_addr_uniform) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(g), "s"(lds_addr_uniform)
+               : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const char* p) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+      (__attribute__((address_space(3))) const char*)p));
+}
+
+// s_waitcnt vmcnt(0) only (expcnt and lgkmcnt left at their maxima)
+__device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // Runs the k loop of one tile.  a_row_ptr(row) / b_row_ptr(row) return the global address of
 // k = 0 of tile row `row` (0..255); rows past the operand's end must be clamped by the functor
 // to some valid row (the epilogue masks them).  nk = number of 128-byte k steps (may be 0).
-// Every thread of the workgroup must call this; it ends with a workgroup barrier.
+// Every thread of the workgroup must call this.  It ends with a workgroup barrier after the last
+// LDS read, so the caller may reuse the LDS buffer at once.
 template <typename T, typename AF, typename BF>
-__device__ __forceinline__ void gemm_tile(floatx16 (&acc)[4][4], AF a_row_ptr, BF b_row_ptr, int nk,
+__device__ __forceinline__ void gemm_tile(floatx16 (&acc)[kIB][kJB], AF a_row_ptr, BF b_row_ptr, int nk,
                                           char* smem) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int ld_row = tid >> 3, ld_chunk = tid & 7;
-
-  const char* ap[8];
-  const char* bp[8];
-  int st_off[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int row = ld_row + 32 * i;
-    ap[i] = a_row_ptr(row) + ld_chunk * 16;
-    bp[i] = b_row_ptr(row) + ld_chunk * 16;
-    st_off[i] = row * kStepBytes + ((ld_chunk << 4) ^ swz16(row));
-  }
-  int rd_a[4], rd_b[4], sw_a[4], sw_b[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int ra = wm * 128 + i * 32 + (lane & 31);
-    const int rb = wn * 128 + i * 32 + (lane & 31);
-    rd_a[i] = ra * kStepBytes;
-    rd_b[i] = kLdsOperand + rb * kStepBytes;
-    sw_a[i] = swz16(ra);
-    sw_b[i] = swz16(rb);
-  }
+  const int wm = wave / kWavesB, wn = wave % kWavesB;
 
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < kIB; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < kJB; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  if (nk <= 0) return;
 
-  if (nk <= 0) {
-    __syncthreads();
-    return;
+  // direct-load sources: lane l of load q covers row wave*32 + q*8 + l/8, physical chunk l%8
+  const char* ap[kLoadsPerWave];
+  const char* bp[kLoadsPerWave];
+#pragma unroll
+  for (int q = 0; q < kLoadsPerWave; ++q) {
+    const int row = wave * kRowsPerWave + q * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ swz(row);
+    ap[q] = a_row_ptr(row) + c * 16;
+    bp[q] = b_row_ptr(row) + c * 16;
   }
+  const uint32_t wave_lds =
+      __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * kRowsPerWave * kStepBytes);
 
-  uint4 ga[8], gb[8];
+  // fragment-read addresses
+  int rd_a[kIB], rd_b[kJB], sw_a[kIB], sw_b[kJB];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    ga[i] = *reinterpret_cast<const uint4*>(ap[i]);
-    gb[i] = *reinterpret_cast<const uint4*>(bp[i]);
+  for (int i = 0; i < kIB; ++i) {
+    const int ra = wm * (kTile / kWavesA) + i * 32 + (lane & 31);
+    rd_a[i] = ra * kStepBytes;
+    sw_a[i] = swz(ra) << 4;
   }
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    *reinterpret_cast<uint4*>(smem + st_off[i]) = ga[i];
-    *reinterpret_cast<uint4*>(smem + kLdsOperand + st_off[i]) = gb[i];
+  for (int j = 0; j < kJB; ++j) {
+    const int rb = wn * (kTile / kWavesB) + j * 32 + (lane & 31);
+    rd_b[j] = kLdsOperand + rb * kStepBytes;
+    sw_b[j] = swz(rb) << 4;
   }
+  const int half16 = (lane >> 5) << 4;
+
+  // each call fetches the next k-step into the given stage
+  auto issue_loads = [&](int stage) {
+    const uint32_t base = wave_lds + stage * kLdsStage;
+#pragma unroll
+    for (int q = 0; q < kLoadsPerWave; ++q) {
+      direct_load16(ap[q], base + q * 8 * kStepBytes);
+      direct_load16(bp[q], base + kLdsOperand + q * 8 * kStepBytes);
+      ap[q] += kStepBytes;
+      bp[q] += kStepBytes;
+    }
+  };
+  uint4 fa[2][kIB], fb[2][kJB];
+  auto read_frags = [&](const char* stage, int ks, int f) {
+    const int cb = (ks << 5) | half16;
+#pragma unroll
+    for (int i = 0; i < kIB; ++i) fa[f][i] = *reinterpret_cast<const uint4*>(stage + rd_a[i] + (cb ^ sw_a[i]));
+#pragma unroll
+    for (int j = 0; j < kJB; ++j) fb[f][j] = *reinterpret_cast<const uint4*>(stage + rd_b[j] + (cb ^ sw_b[j]));
+  };
+  auto mfmas = [&](int f) {
+#pragma unroll
+    for (int i = 0; i < kIB; ++i)
+#pragma unroll
+      for (int j = 0; j < kJB; ++j) Mma<T>::run(fa[f][i], fb[f][j], acc[i][j]);
+  };
+
+  issue_loads(0);
+  if (nk > 1) issue_loads(1);
+  wait_direct_loads();
   __syncthreads();
+  read_frags(smem, 0, 0);
 
   for (int kt = 0; kt < nk; ++kt) {
-    char* cur = smem + (kt & 1) * kLdsStage;
-    char* nxt = smem + ((kt + 1) & 1) * kLdsStage;
-    const bool more = (kt + 1 < nk);
-    if (more) {
-      const size_t kb = static_cast<size_t>(kt + 1) * kStepBytes;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        ga[i] = *reinterpret_cast<const uint4*>(ap[i] + kb);
-        gb[i] = *reinterpret_cast<const uint4*>(bp[i] + kb);
-      }
-    }
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const int cb = (ks * 2 + (lane >> 5)) << 4;
-      uint4 fa[4], fb[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        fa[i] = *reinterpret_cast<const uint4*>(cur + rd_a[i] + (cb ^ sw_a[i]));
-        fb[i] = *reinterpret_cast<const uint4*>(cur + rd_b[i] + (cb ^ sw_b[i]));
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) Mma<T>::run(fa[i], fb[j], acc[i][j]);
-    }
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        *reinterpret_cast<uint4*>(nxt + st_off[i]) = ga[i];
-        *reinterpret_cast<uint4*>(nxt + kLdsOperand + st_off[i]) = gb[i];
-      }
-    }
-    __syncthreads();
+    const int cs = kt & 1;
+    const char* cur = smem + cs * kLdsStage;
+    const char* nxt = smem + (cs ^ 1) * kLdsStage;
+    read_frags(cur, 1, 1);
+    mfmas(0);
+    read_frags(cur, 2, 0);
+    mfmas(1);
+    read_frags(cur, 3, 1);
+    mfmas(0);
+    wait_direct_loads();   // this wavefront's loads into `nxt` have landed
+    __syncthreads();       // everyone's have, and everyone holds its last fragments of `cur`
+    if (kt + 2 < nk) issue_loads(cs);
+    if (kt + 1 < nk) read_frags(nxt, 0, 0);
+    mfmas(1);
   }
 }
 

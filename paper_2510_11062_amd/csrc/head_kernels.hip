@@ -1,7 +1,7 @@
 // LM-head kernels of the AT-GRPO policy loss (gfx950).
 //
 // Forward (log pi_theta(y_t) inside the ratio of Eq. 2): logits tiles z[v, t] = <W[v], hidden[t]>
-// are produced in MFMA accumulators, reduced to per-(vocab half-tile, token) (max, sum-exp)
+// are produced in MFMA accumulators, reduced to per-(vocabulary tile, token) (max, sum-exp)
 // partials and the target logit, and discarded.  A small combine kernel turns the partials into
 // lse and logp.
 //
@@ -42,20 +42,22 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
   const TileCoord tc;
   const size_t row_bytes = static_cast<size_t>(H) * sizeof(T);
   const int nk = static_cast<int>(row_bytes / kStepBytes);
+  float* red_m = reinterpret_cast<float*>(smem);          // [kWavesA][256]
+  float* red_s = red_m + kWavesA * kTile;                 // [kWavesA][256]
 
   for (int t = logical_workgroup(); t < total; t += gridDim.x) {
     int vt, tt;
     ord.decode(t, &vt, &tt);
     const int v0 = vt * kTile, t0 = tt * kTile;
 
-    int tcol[4], ycol[4];
+    int tcol[kJB], ycol[kJB];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < kJB; ++j) {
       tcol[j] = t0 + tc.b_row(j);
       ycol[j] = (tcol[j] < n) ? token_id[idx[c0 + tcol[j]]] : -1;
     }
 
-    floatx16 acc[4][4];
+    floatx16 acc[kIB][kJB];
     gemm_tile<T>(
         acc,
         [&](int row) {
@@ -68,22 +70,22 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
         },
         nk, smem);
 
-    const int vbase = v0 + tc.wm * 128;        // first vocab row this wavefront holds
-    const int vrem = V - vbase;                // rows of it that exist (may be <= 0)
-    const bool ragged = vrem < 128;
-    const size_t prow = static_cast<size_t>(vt * 2 + tc.wm) * TC;
+    constexpr int kWaveRows = kTile / kWavesA;   // vocab rows one wavefront holds
+    const int vbase = v0 + tc.wm * kWaveRows;
+    const int vrem = V - vbase;                  // rows of it that exist (may be <= 0)
+    const bool ragged = vrem < kWaveRows;
 
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < kJB; ++j) {
       float mx = -INFINITY;
       if (!ragged) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < kIB; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[i][j][r]);
       } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < kIB; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int vl = i * 32 + 8 * (r >> 2) + 4 * tc.half + (r & 3);
@@ -95,12 +97,12 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
       float sum = 0.f;
       if (!ragged) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < kIB; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[i][j][r], kLog2e, -m2));
       } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < kIB; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int vl = i * 32 + 8 * (r >> 2) + 4 * tc.half + (r & 3);
@@ -108,17 +110,17 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
           }
       }
       sum += __shfl_xor(sum, 32, 64);
-      if (tc.half == 0 && tcol[j] < n) {
-        part_m[prow + tcol[j]] = (mx == -INFINITY) ? -INFINITY : m2;
-        part_s[prow + tcol[j]] = sum;
+      if (tc.half == 0) {
+        red_m[tc.wm * kTile + tc.b_row(j)] = (mx == -INFINITY) ? -INFINITY : m2;
+        red_s[tc.wm * kTile + tc.b_row(j)] = sum;
       }
       // target logit: held by exactly one lane of one wavefront of one tile
       const int rel = ycol[j] - vbase;
-      const bool hit = (tcol[j] < n) && rel >= 0 && rel < 128 && (((rel >> 2) & 1) == tc.half);
+      const bool hit = (tcol[j] < n) && rel >= 0 && rel < kWaveRows && (((rel >> 2) & 1) == tc.half);
       if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
         float zt = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < kIB; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int vl = i * 32 + 8 * (r >> 2) + (r & 3);   // half bit compared separately
@@ -127,6 +129,22 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
         if (hit) zy[tcol[j]] = zt;
       }
     }
+    // fold the four vocabulary quarters of the tile: one (max, sum) per token and vocabulary tile
+    __syncthreads();
+    if (threadIdx.x < kTile && t0 + threadIdx.x < n) {
+      float M = -INFINITY;
+#pragma unroll
+      for (int q = 0; q < kWavesA; ++q) M = fmaxf(M, red_m[q * kTile + threadIdx.x]);
+      float S = 0.f;
+#pragma unroll
+      for (int q = 0; q < kWavesA; ++q) {
+        const float mq = red_m[q * kTile + threadIdx.x];
+        if (mq != -INFINITY) S += red_s[q * kTile + threadIdx.x] * fast_exp2(mq - M);
+      }
+      part_m[static_cast<size_t>(vt) * TC + t0 + threadIdx.x] = M;
+      part_s[static_cast<size_t>(vt) * TC + t0 + threadIdx.x] = S;
+    }
+    __syncthreads();
   }
 }
 
@@ -230,6 +248,9 @@ struct Pack4<bf16_t> {
   }
 };
 
+constexpr int kDzRowStride = kTile * 2 + 8;              // bytes; +8 keeps the 8-byte stores conflict-free
+constexpr int kDzLdsBytes = kTile * kDzRowStride;        // bf16 dZ tile staged for coalesced stores
+
 template <typename T>
 __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
     const T* __restrict__ hidden, const T* __restrict__ W, const int32_t* __restrict__ idx,
@@ -244,16 +265,17 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
   const TileCoord tc;
   const size_t row_bytes = static_cast<size_t>(H) * sizeof(T);
   const int nk = static_cast<int>(row_bytes / kStepBytes);
+  constexpr bool kStage = sizeof(T) == 2;      // bf16: dZ[t][v] goes through LDS for 16-byte stores
 
   for (int t = logical_workgroup(); t < total; t += gridDim.x) {
     int vt, tt;
     ord.decode(t, &vt, &tt);
     const int v0 = vt * kTile, t0 = tt * kTile;
 
-    int tcol[4], ycol[4];
-    float gcol[4], l2col[4];
+    int tcol[kJB], ycol[kJB];
+    float gcol[kJB], l2col[kJB];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < kJB; ++j) {
       tcol[j] = t0 + tc.b_row(j);
       if (tcol[j] < n) {
         const int row = idx[c0 + tcol[j]];
@@ -267,7 +289,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
       }
     }
 
-    floatx16 acc[4][4];
+    floatx16 acc[kIB][kJB];
     gemm_tile<T>(
         acc,
         [&](int row) {
@@ -280,29 +302,58 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
         },
         nk, smem);
 
-    const int vbase = v0 + tc.wm * 128;
+    const int vwave = tc.wm * (kTile / kWavesA);     // first vocab row (inside the tile) of this wavefront
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < kJB; ++j) {
       const float g = gcol[j];
+      const bool live = tcol[j] < n;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < kIB; ++i) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int v = vbase + i * 32 + 8 * q + 4 * tc.half;   // first of 4 consecutive vocab rows
+          const int vl = vwave + i * 32 + 8 * q + 4 * tc.half;   // first of 4 consecutive vocab rows
+          const int v = v0 + vl;
           float d[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float p = fast_exp2(fmaf(acc[i][j][q * 4 + e], kLog2e, -l2col[j]));
             float x = -g * p;
             if (v + e == ycol[j]) x += g;
-            d[e] = (v + e < V && tcol[j] < n) ? x : 0.f;   // k padding and rows past the count are 0
+            d[e] = (v + e < V && live) ? x : 0.f;   // k padding and rows past the count are 0
           }
-          if (v < Vp) Pack4<T>::store(dZ + static_cast<size_t>(tcol[j]) * Vp + v, d[0], d[1], d[2], d[3]);
+          if (kStage) {
+            uint2 u;
+            u.x = static_cast<uint32_t>(f32_to_bf16(d[0]).bits) | (static_cast<uint32_t>(f32_to_bf16(d[1]).bits) << 16);
+            u.y = static_cast<uint32_t>(f32_to_bf16(d[2]).bits) | (static_cast<uint32_t>(f32_to_bf16(d[3]).bits) << 16);
+            *reinterpret_cast<uint2*>(smem + tc.b_row(j) * kDzRowStride + vl * 2) = u;
+          } else {
+            if (v < Vp) Pack4<T>::store(dZ + static_cast<size_t>(tcol[j]) * Vp + v, d[0], d[1], d[2], d[3]);
+          }
 #pragma unroll
           for (int e = 0; e < 4; ++e)
             if (v + e < V) dZt[static_cast<size_t>(v + e) * TC + tcol[j]] = from_f32<T>(d[e]);
         }
       }
+    }
+    if (kStage) {
+      __syncthreads();
+      // copy the staged tile out: 32 threads x 16 bytes cover the 512 bytes of one token row
+      const int col16 = threadIdx.x & 31;
+      const int v = v0 + col16 * 8;
+      if (v < Vp) {
+#pragma unroll 4
+        for (int it = 0; it < kTile / 16; ++it) {
+          const int row = it * 16 + (threadIdx.x >> 5);
+          const char* src = smem + row * kDzRowStride + col16 * 16;
+          uint4 u;
+          const uint2 lo = *reinterpret_cast<const uint2*>(src);
+          const uint2 hi = *reinterpret_cast<const uint2*>(src + 8);
+          u.x = lo.x; u.y = lo.y; u.z = hi.x; u.w = hi.y;
+          *reinterpret_cast<uint4*>(reinterpret_cast<char*>(dZ) +
+                                    (static_cast<size_t>(t0 + row) * Vp + v) * 2) = u;
+        }
+      }
+      __syncthreads();
     }
   }
 }
@@ -330,7 +381,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dh(const T* __restrict__ 
     int tt, ht;
     ord.decode(t, &tt, &ht);
     const int t0 = tt * kTile, h0 = ht * kTile;
-    floatx16 acc[4][4];
+    floatx16 acc[kIB][kJB];
     gemm_tile<T>(
         acc,
         [&](int row) { return reinterpret_cast<const char*>(dZ) + static_cast<size_t>(t0 + row) * row_bytes; },
@@ -340,14 +391,14 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dh(const T* __restrict__ 
         },
         nk, smem);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < kIB; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int j = t0 + tc.a_row(i, r);
         if (j >= n) continue;
         T* out = d_hidden + static_cast<size_t>(idx[c0 + j]) * H;
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
+        for (int jj = 0; jj < kJB; ++jj) {
           const int h = h0 + tc.b_row(jj);
           if (h < H) out[h] = from_f32<T>(acc[i][jj][r]);
         }
@@ -378,7 +429,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dw(const T* __restrict__ 
     int vt, ht;
     ord.decode(t, &vt, &ht);
     const int v0 = vt * kTile, h0 = ht * kTile;
-    floatx16 acc[4][4];
+    floatx16 acc[kIB][kJB];
     gemm_tile<T>(
         acc,
         [&](int row) {
@@ -391,14 +442,14 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dw(const T* __restrict__ 
         },
         nk, smem);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < kIB; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int v = v0 + tc.a_row(i, r);
         if (v >= V) continue;
         float* out = dW + static_cast<size_t>(v) * H;
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
+        for (int jj = 0; jj < kJB; ++jj) {
           const int h = h0 + tc.b_row(jj);
           if (h < H) out[h] = accumulate ? out[h] + acc[i][jj][r] : acc[i][jj][r];
         }
@@ -407,9 +458,9 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dw(const T* __restrict__ 
 }
 
 template <typename K>
-int allow_big_lds(K kernel) {
+int allow_big_lds(K kernel, int bytes = kLdsBytes) {
   ATG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
   return AT_GRPO_OK;
 }
 
@@ -448,7 +499,7 @@ int launch_lse_combine(const HeadGeom& g, const HeadChunk& ch, const float* part
                        const float* zy, float* logp, float* lse, hipStream_t s) {
   ProfScope ps(PROF_LSE_COMBINE, s);
   hipLaunchKernelGGL(k_lse_combine, dim3(g.TC / 64), dim3(256), 0, s, ch.idx, ch.cnt, ch.c0, g.TC,
-                     2 * g.n_vtiles, part_m, part_s, zy, logp, lse);
+                     g.n_vtiles, part_m, part_s, zy, logp, lse);
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }
@@ -490,8 +541,9 @@ int launch_head_dz(const HeadGeom& g, const HeadChunk& ch, const void* hidden, c
   ProfScope ps(PROF_HEAD_DZ, s);
   if (g.dtype == AT_GRPO_BF16) {
     auto k = k_head_dz<bf16_t>;
-    ATG_TRY(allow_big_lds(k));
-    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
+    constexpr int lds = kDzLdsBytes > kLdsBytes ? kDzLdsBytes : kLdsBytes;
+    ATG_TRY(allow_big_lds(k, lds));
+    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), lds, s,
                        static_cast<const bf16_t*>(hidden), static_cast<const bf16_t*>(W), ch.idx, ch.cnt,
                        ch.c0, token_id, lse, coef, static_cast<bf16_t*>(dZ), static_cast<bf16_t*>(dZt),
                        g.H, g.V, g.Vp, g.TC, g.n_vtiles);

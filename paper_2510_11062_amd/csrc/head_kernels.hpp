@@ -23,7 +23,7 @@ struct HeadChunk {
   int32_t c0;           // first list position of this super-chunk
 };
 
-// part_m / part_s: [2 * n_vtiles][TC] per-(vocab half-tile, token) running max (log2 domain) and
+// part_m / part_s: [n_vtiles][TC] per-(vocabulary tile, token) running max (log2 domain) and
 // sum; zy: [TC] target logit.  hidden / W are the caller's tensors.
 int launch_head_fwd(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
                     const int32_t* token_id, float* part_m, float* part_s, float* zy,
