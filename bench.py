@@ -22,30 +22,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-from paper_2510_11062_amd import api, rollout_standin, synth  # noqa: E402
+from paper_2510_11062_amd import api, synth, workload  # noqa: E402
 
 PEAK = {"bf16": 2500.0, "f32": 157.3}      # dense MFMA TFLOP/s, MI355X data sheet
-
-
-def build_inputs(cfg, dev):
-    st = synth.make_structure(cfg)
-    hidden, W = synth.make_tensors(cfg, st.n_tok, device=dev)
-    u, noise = synth.make_rollout_randoms(cfg, st.n_tok, device=dev)
-    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
-    cu = torch.from_numpy(st.cu_seqlens).to(dev)
-    lengths = torch.from_numpy(st.lengths).to(dev)
-    resp_of_tok = torch.repeat_interleave(torch.arange(len(st.lengths), device=dev), cu[1:] - cu[:-1])
-    mask = None if st.mask is None else torch.from_numpy(st.mask).to(dev)
-    valid = torch.ones(st.n_tok, dtype=torch.bool, device=dev) if mask is None else mask.bool()
-    head_of_resp = torch.from_numpy(st.head_of_agent[st.agent_id].astype(np.int64)).to(dev)
-    head_of_tok = head_of_resp[resp_of_tok]
-    token_id, old_logp = rollout_standin.draw_tokens_and_old_logp(hidden, W, head_of_tok, valid, u, noise)
-    del u, noise
-    multi = cfg.n_heads > 1
-    batch = api.Batch(hidden, W, token_id, cu, mask, i32(st.agent_id) if multi else None,
-                      i32(st.head_of_agent) if multi else None)
-    ids = (i32(st.env_id), i32(st.agent_id), i32(st.turn_id), torch.from_numpy(st.reward).to(dev))
-    return st, batch, ids, old_logp, resp_of_tok, valid, lengths
 
 
 def cpu_baseline(cfg, st, batch, old_logp, n_sample):
@@ -93,8 +72,9 @@ def main():
     cfg = synth.CONFIGS[args.config]
     api.load_library()
 
-    st, batch, ids, old_logp, resp_of_tok, valid, lengths = build_inputs(cfg, dev)
-    env_id, agent_id, turn_id, reward = ids
+    wl = workload.build(cfg, dev)
+    st, batch, old_logp, resp_of_tok, valid = wl.st, wl.batch, wl.old_logp, wl.resp_of_tok, wl.valid
+    env_id, agent_id, turn_id, reward = wl.env_id, wl.agent_id, wl.turn_id, wl.reward
     eps = cfg.eps_clip
 
     d_hidden = torch.empty_like(batch.hidden)

@@ -329,18 +329,19 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
           } else {
             if (v < Vp) Pack4<T>::store(dZ + static_cast<size_t>(tcol[j]) * Vp + v, d[0], d[1], d[2], d[3]);
           }
+          if (!kStage) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (v + e < V) dZt[static_cast<size_t>(v + e) * TC + tcol[j]] = from_f32<T>(d[e]);
+            for (int e = 0; e < 4; ++e)
+              if (v + e < V) dZt[static_cast<size_t>(v + e) * TC + tcol[j]] = from_f32<T>(d[e]);
+          }
         }
       }
     }
     if (kStage) {
       __syncthreads();
-      // copy the staged tile out: 32 threads x 16 bytes cover the 512 bytes of one token row
+      // dZ[t][v]: 32 threads x 16 bytes cover the 512 bytes of one token row of the staged tile
       const int col16 = threadIdx.x & 31;
-      const int v = v0 + col16 * 8;
-      if (v < Vp) {
+      if (v0 + col16 * 8 < Vp) {
 #pragma unroll 4
         for (int it = 0; it < kTile / 16; ++it) {
           const int row = it * 16 + (threadIdx.x >> 5);
@@ -350,7 +351,26 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
           const uint2 hi = *reinterpret_cast<const uint2*>(src + 8);
           u.x = lo.x; u.y = lo.y; u.z = hi.x; u.w = hi.y;
           *reinterpret_cast<uint4*>(reinterpret_cast<char*>(dZ) +
-                                    (static_cast<size_t>(t0 + row) * Vp + v) * 2) = u;
+                                    (static_cast<size_t>(t0 + row) * Vp + v0 + col16 * 8) * 2) = u;
+        }
+      }
+      // dZt[v][t]: the same staged tile read column-wise; a thread owns one vocabulary row and half
+      // of the tile's tokens, 8 tokens (16 bytes) per store
+      const int vrow = threadIdx.x & (kTile - 1);
+      const int thalf = (threadIdx.x >> 8) * (kTile / 2);
+      if (v0 + vrow < V) {
+        char* dst = reinterpret_cast<char*>(dZt) + (static_cast<size_t>(v0 + vrow) * TC + t0 + thalf) * 2;
+        const char* col = smem + thalf * kDzRowStride + vrow * 2;
+#pragma unroll 4
+        for (int tb = 0; tb < kTile / 16; ++tb) {
+          uint32_t w[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const uint32_t a = *reinterpret_cast<const uint16_t*>(col + (tb * 8 + 2 * e) * kDzRowStride);
+            const uint32_t b = *reinterpret_cast<const uint16_t*>(col + (tb * 8 + 2 * e + 1) * kDzRowStride);
+            w[e] = a | (b << 16);
+          }
+          *reinterpret_cast<uint4*>(dst + tb * 16) = make_uint4(w[0], w[1], w[2], w[3]);
         }
       }
       __syncthreads();

@@ -11,6 +11,16 @@ from __future__ import annotations
 import torch
 
 
+def _logits_fp32(h, W):
+    """h W^T with fp32 results (fp32 accumulation of the stored input values)."""
+    if h.dtype == torch.float32:
+        return h @ W.T
+    try:
+        return torch.mm(h, W.T, out_dtype=torch.float32)
+    except (TypeError, RuntimeError):
+        return h.float() @ W.float().T
+
+
 @torch.no_grad()
 def draw_tokens_and_old_logp(hidden, W_list, head_of_tok, valid, u, noise, rows_per_chunk: int = 4096):
     """hidden [n, H]; W_list of [V, H]; head_of_tok int64 [n]; valid bool [n]; u float64 [n] in
@@ -22,14 +32,12 @@ def draw_tokens_and_old_logp(hidden, W_list, head_of_tok, valid, u, noise, rows_
     old_logp = torch.zeros(n, dtype=torch.float32, device=dev)
     for k, W in enumerate(W_list):
         rows = torch.nonzero(valid & (head_of_tok == k)).squeeze(1)
-        Wf = W.float()
         for s in range(0, rows.numel(), rows_per_chunk):
             r = rows[s:s + rows_per_chunk]
-            logits = hidden[r].float() @ Wf.T
+            logits = _logits_fp32(hidden[r], W)
             logp = torch.log_softmax(logits, dim=1)
             cdf = torch.cumsum(torch.exp(logp), dim=1)
             y = torch.searchsorted(cdf, u[r].float().unsqueeze(1)).squeeze(1).clamp_(max=W.shape[0] - 1)
             token_id[r] = y.to(torch.int32)
             old_logp[r] = logp.gather(1, y.unsqueeze(1)).squeeze(1) + noise[r]
-        del Wf
     return token_id, old_logp

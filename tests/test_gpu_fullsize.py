@@ -1,0 +1,161 @@
+"""Parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+
+The fp64 oracle cannot run a whole batch at V = 151936 (about 2-4 GFLOP per token), so the checks are:
+  * everything that is cheap on the CPU is compared in full (grouping, advantages, the surrogate
+    stage on synthetic log-probs, counts);
+  * log-probs, log-sum-exp and d_hidden rows are compared on a seeded sample of tokens per head, which
+    the oracle computes one by one from the same input bits;
+  * properties that hold at any size tie the rest down: the on-policy identity loss = -mean(A),
+    exact zeros where no gradient can flow, sum_v dW[v, :] = 0, and the pairing identity
+    <d_hidden, hidden> = <dW, W> (both equal <dZ, Z>).
+Sampled tokens and old log-probs come from the torch rollout stand-in, never from the library.
+"""
+import sys
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import at_grpo_oracle as orc
+from paper_2510_11062_amd import api, synth, workload
+from tests.gpu_case import host
+
+SAMPLES_PER_HEAD = 40
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def oracle_full_advantages(st, cfg):
+    key = orc.group_key(st.env_id, st.agent_id, st.turn_id, cfg.N, cfg.T)
+    gid, G, offs, perm = orc.group_segments(key)
+    adv, mean, std = orc.group_advantage(st.reward, gid, G)
+    return gid, G, offs, perm, adv
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_full_size_sampled_parity_and_invariants(gpu_device, name):
+    cfg = synth.CONFIGS[name]
+    dev = gpu_device
+    eps = cfg.eps_clip
+    say(f"[full] {name}: building inputs")
+    wl = workload.build(cfg, dev, keep_noise=True)
+    st = wl.st
+    n_valid_total = int(wl.valid.sum())
+    say(f"[full] {name}: {n_valid_total} response tokens in {st.n_tok} rows, {cfg.n_heads} head(s)")
+
+    # ---- S1 + S2 in full
+    gid, G, offs, perm, adv64 = oracle_full_advantages(st, cfg)
+    ga = api.at_grpo_group_advantage(wl.env_id, wl.agent_id, wl.turn_id, wl.reward, cfg.E, cfg.N, cfg.T)
+    torch.cuda.synchronize()
+    assert api.error_word(ga["workspace"]) == 0
+    assert int(ga["n_groups"]) == G
+    assert np.array_equal(host(ga["group_id"]), gid)
+    assert np.array_equal(host(ga["seg_offsets"])[:G + 1], offs)
+    assert np.array_equal(host(ga["perm"]), perm)
+    adv_gpu = host(ga["adv"]).astype(np.float64)
+    assert np.all(adv_gpu[adv64 == 0] == 0) and np.allclose(adv_gpu, adv64, rtol=1e-4, atol=1e-6)
+    adv32 = adv64.astype(np.float32)
+    adv_dev = torch.from_numpy(adv32).to(dev)        # oracle advantages feed both sides below
+
+    # ---- S5 + S6 in full on synthetic log-probs (stage parity: masks bit-exact)
+    say(f"[full] {name}: surrogate stage")
+    logp_in = (wl.old_logp + 1.5 * wl.noise).contiguous()
+    layout = api.Batch(None, None, wl.batch.token_id, wl.batch.cu_seqlens, wl.batch.mask, wl.batch.resp_agent,
+                       wl.batch.head_of_agent, n_tok=st.n_tok, V=cfg.V, n_heads=cfg.n_heads)
+    sur = api.at_grpo_surrogate_from_logp(layout, logp_in, wl.old_logp, adv_dev, eps, eps)
+    torch.cuda.synchronize()
+    resp_of_tok, head_of_tok = orc.token_heads(st.n_tok, st.cu_seqlens, st.agent_id,
+                                               st.head_of_agent if cfg.n_heads > 1 else None)
+    ref = orc.policy_loss_from_logp(host(logp_in), host(wl.old_logp), adv32, st.mask, head_of_tok, resp_of_tok,
+                                    cfg.n_heads, eps, eps)
+    assert np.array_equal(host(sur["clip_mask"]), ref[1])
+    assert np.array_equal(host(sur["n_valid"]), ref[2])
+    assert np.all(np.abs(host(sur["loss"]) - ref[0]) <= 1e-4 * np.abs(ref[0]) + 1e-6)
+
+    # ---- forward in full, sampled parity
+    say(f"[full] {name}: forward")
+    fwd = api.at_grpo_policy_loss_fwd(wl.batch, wl.old_logp, adv_dev, eps, eps)
+    torch.cuda.synchronize()
+    assert api.error_word(fwd["workspace"]) == 0
+    assert np.array_equal(host(fwd["n_valid"]), ref[2])
+    logp_gpu, lse_gpu = host(fwd["logp"]), host(fwd["lse"])
+    valid_np = host(wl.valid)
+    assert np.all(logp_gpu[~valid_np] == 0) and np.all(host(fwd["clip_mask"])[~valid_np] == 0)
+    rng = np.random.default_rng(cfg.seed)
+    lo32, hi32 = orc.clip_thresholds(eps, eps)
+    old_np = host(wl.old_logp)
+    tok_np = host(wl.batch.token_id)
+    samples = {}
+    for k in range(cfg.n_heads):
+        rows = np.nonzero(valid_np & (head_of_tok == k))[0]
+        pick = np.sort(rng.choice(rows, size=min(SAMPLES_PER_HEAD, rows.size), replace=False))
+        # always include the first and the last row of the head's list (tile edges)
+        pick = np.unique(np.concatenate([pick, rows[:1], rows[-1:]]))
+        say(f"[full] {name}: oracle on {pick.size} sampled tokens of head {k}")
+        W64 = host(wl.batch.W[k]).astype(np.float64)
+        h_rows = host(wl.batch.hidden[torch.from_numpy(pick).to(dev)])
+        lp, ls = orc.token_logprob_single(h_rows, W64, tok_np[pick])
+        assert np.abs(logp_gpu[pick] - lp).max() <= 1e-2
+        assert np.abs(lse_gpu[pick] - ls).max() <= 1e-2
+        samples[k] = (pick, W64, h_rows, lp)
+    say(f"[full] {name}: max sampled |dlogp| = "
+        f"{max(np.abs(logp_gpu[p] - lp).max() for p, _, _, lp in samples.values()):.2e}")
+
+    # on-policy identity: with old = current the loss is minus the token mean of the advantages
+    on = api.at_grpo_policy_loss_fwd(wl.batch, fwd["logp"].clone(), adv_dev, eps, eps)
+    torch.cuda.synchronize()
+    assert int(on["clip_mask"].max()) == 0
+    A_tok = adv64[np.maximum(resp_of_tok, 0)]
+    for k in range(cfg.n_heads):
+        rows = valid_np & (head_of_tok == k)
+        expect = -A_tok[rows].mean()
+        assert abs(float(on["loss"][k]) - expect) <= 2e-2 * abs(expect) + 1e-5
+
+    # ---- backward in full
+    say(f"[full] {name}: backward")
+    grad_loss = None
+    bwd = api.at_grpo_policy_loss_bwd(wl.batch, wl.old_logp, adv_dev, fwd["logp"], fwd["lse"], eps, eps)
+    torch.cuda.synchronize()
+    assert api.error_word(bwd["workspace"]) == 0
+    dH = bwd["d_hidden"]
+    # rows that cannot carry gradient are exactly zero
+    dead = (~wl.valid) | (adv_dev[wl.resp_of_tok] == 0) | ((fwd["clip_mask"] & 4) != 0)
+    assert float(dH[dead].abs().max()) == 0.0 if bool(dead.any()) else True
+    live = ~dead
+    assert bool((dH[live].abs().amax(dim=1) > 0).all())
+    n_valid_head = ref[2]
+    for k in range(cfg.n_heads):
+        pick, W64, h_rows, lp = samples[k]
+        d = lp.astype(np.float32) - old_np[pick]
+        near = (np.abs(d - lo32) <= 1e-3) | (np.abs(d - hi32) <= 1e-3)
+        l, ratio, cm, sel = orc.surrogate_terms(lp, old_np[pick], A_tok[pick], eps, eps)
+        assert np.array_equal(cm[~near], host(fwd["clip_mask"])[pick][~near])
+        g = -(1.0 / n_valid_head[k]) * A_tok[pick] * ratio * sel
+        dh_ref, _ = orc.head_backward_single(h_rows, W64, tok_np[pick], g)
+        got = host(dH[torch.from_numpy(pick).to(dev)]).astype(np.float64)
+        keep = ~near
+        err = np.linalg.norm(got[keep] - dh_ref[keep]) / max(np.linalg.norm(dh_ref[keep]), 1e-30)
+        say(f"[full] {name}: head {k} sampled d_hidden rel err {err:.3e}")
+        assert err <= 2e-2
+        assert np.all(got[keep][g[keep] == 0] == 0)
+        del W64
+    # gradient invariants at full size
+    for k in range(cfg.n_heads):
+        dWk = bwd["dW"][k]
+        scale = float(dWk.abs().sum(dim=0).max())
+        resid = float(dWk.sum(dim=0).abs().max())
+        rows_k = wl.valid & (wl.head_of_tok == k)
+        per_row = (dH[rows_k].float() * wl.batch.hidden[rows_k].float()).sum(dim=1, dtype=torch.float64)
+        lhs, mass = float(per_row.sum()), float(per_row.abs().sum())
+        rhs = float((dWk * wl.batch.W[k].float()).sum(dtype=torch.float64))
+        say(f"[full] {name}: head {k} sum_v dW residual {resid:.2e} (column mass {scale:.2e}); "
+            f"<dH,H> = {lhs:.6e}, <dW,W> = {rhs:.6e}, row mass {mass:.3e}")
+        assert resid <= 2e-2 * scale
+        assert abs(lhs - rhs) <= 2e-2 * mass + 1e-9
+    api.release_workspace()
+    torch.cuda.empty_cache()
