@@ -152,7 +152,7 @@ void make_plan(const at_grpo_batch* b, int call, WsAlloc& ws, Plan* p) {
     p->Wt = ws.take<char>(static_cast<size_t>(g.H) * g.Vp * g.esize);
     p->hT = ws.take<char>(static_cast<size_t>(g.H) * g.TC * g.esize);
     p->dZ = ws.take<char>(static_cast<size_t>(g.TC) * g.Vp * g.esize);
-    p->dZt = ws.take<char>(static_cast<size_t>(g.V) * g.TC * g.esize);
+    p->dZt = (g.dtype == AT_GRPO_F32) ? ws.take<char>(static_cast<size_t>(g.V) * g.TC * g.esize) : nullptr;
   }
 }
 
@@ -280,7 +280,7 @@ extern "C" int at_grpo_policy_loss_bwd(const at_grpo_batch* batch, const float* 
       ATG_TRY(launch_head_dz(p.g, ch, batch->hidden, batch->W[m], batch->token_id, lse, p.coef, p.dZ,
                              p.dZt, s));
       ATG_TRY(launch_head_dh(p.g, ch, p.dZ, p.Wt, d_hidden, s));
-      ATG_TRY(launch_head_dw(p.g, ch, p.dZt, p.hT, dW[m], (accumulate_dW != 0 || c > 0) ? 1 : 0,
+      ATG_TRY(launch_head_dw(p.g, ch, p.dZ, p.dZt, p.hT, dW[m], (accumulate_dW != 0 || c > 0) ? 1 : 0,
                              c == 0 ? 1 : 0, s));
     }
   }

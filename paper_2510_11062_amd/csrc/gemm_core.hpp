@@ -197,6 +197,134 @@ __device__ __forceinline__ void gemm_tile(floatx16 (&acc)[kIB][kJB], AF a_row_pt
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Same tile contraction for operands stored k-major (bf16 only):
+//   C[a, b] = sum_k A[k, a] * B[k, b],   A rows and B rows contiguous along a / b.
+// A k-step is 64 rows of 512 bytes (256 columns) per operand.  Direct loads bring two rows per
+// instruction; fragments are fetched with the transposing LDS read ds_read_b64_tr_b16: inside each
+// group of 16 lanes, lane 4r + q supplies the address of 4 consecutive columns of row r (r = 0..3)
+// and lane i receives column i of those four rows, i.e. 4 consecutive k for one column; two reads
+// give the 8 k-values an MFMA lane needs.  The 16-byte chunk index C of row k is stored at
+// (C & 16) | ((C + 4 * (k & 3)) & 15), which makes every transposing read conflict-free.
+// ------------------------------------------------------------------------------------------------
+typedef __bf16 bf16x4_t __attribute__((__vector_size__(4 * sizeof(__bf16))));
+constexpr int kKmRows = 64;                        // k rows per step
+constexpr int kKmRowBytes = kTile * 2;             // 512 bytes of columns per row
+
+__device__ __forceinline__ uint2 lds_read_tr16(const char* p) {
+  const bf16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+      (__attribute__((address_space(3))) bf16x4_t*)(__attribute__((address_space(3))) const char*)p);
+  return __builtin_bit_cast(uint2, v);
+}
+
+// a0 / b0: address of element [k = 0][first column of the tile]; a_ld / b_ld: row strides in bytes;
+// a_cmax / b_cmax: last 16-byte column chunk (0..31) that may be read (columns past it are fetched from
+// that chunk instead and must be masked by the caller); nk: number of 64-row k-steps.
+__device__ __forceinline__ void gemm_tile_kmajor(floatx16 (&acc)[kIB][kJB], const char* a0, size_t a_ld,
+                                                 int a_cmax, const char* b0, size_t b_ld, int b_cmax, int nk,
+                                                 char* smem) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave / kWavesB, wn = wave % kWavesB;
+
+#pragma unroll
+  for (int i = 0; i < kIB; ++i)
+#pragma unroll
+    for (int j = 0; j < kJB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  if (nk <= 0) return;
+
+  // direct loads: instruction q of this wavefront fills rows 2*(wave*4+q), +1; lane -> (row parity, chunk)
+  const char* ap[kLoadsPerWave];
+  const char* bp[kLoadsPerWave];
+#pragma unroll
+  for (int q = 0; q < kLoadsPerWave; ++q) {
+    const int k = (wave * kLoadsPerWave + q) * 2 + (lane >> 5);
+    const int P = lane & 31;
+    const int C = (P & 16) | ((P - 4 * (k & 3)) & 15);
+    ap[q] = a0 + static_cast<size_t>(k) * a_ld + min(C, a_cmax) * 16;
+    bp[q] = b0 + static_cast<size_t>(k) * b_ld + min(C, b_cmax) * 16;
+  }
+  const size_t a_step = a_ld * kKmRows, b_step = b_ld * kKmRows;
+  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * kLoadsPerWave * 1024);
+
+  // fragment addresses: group g = lane/16 -> (column half g&1, k half g>>1); L = lane%16 -> (r, q)
+  const int g = lane >> 4, L = lane & 15, r = L >> 2, qq = L & 3;
+  int rd_a[kIB], rd_b[kJB];
+#pragma unroll
+  for (int i = 0; i < kIB; ++i) {
+    const int m = wm * (kTile / kWavesA) + i * 32 + 16 * (g & 1) + 4 * qq;
+    const int C = m >> 3;
+    const int P = (C & 16) | ((C + 4 * r) & 15);
+    rd_a[i] = (8 * (g >> 1) + r) * kKmRowBytes + P * 16 + (m & 7) * 2;
+  }
+#pragma unroll
+  for (int j = 0; j < kJB; ++j) {
+    const int m = wn * (kTile / kWavesB) + j * 32 + 16 * (g & 1) + 4 * qq;
+    const int C = m >> 3;
+    const int P = (C & 16) | ((C + 4 * r) & 15);
+    rd_b[j] = kLdsOperand + (8 * (g >> 1) + r) * kKmRowBytes + P * 16 + (m & 7) * 2;
+  }
+
+  auto issue_loads = [&](int stage) {
+    const uint32_t base = wave_lds + stage * kLdsStage;
+#pragma unroll
+    for (int q = 0; q < kLoadsPerWave; ++q) {
+      direct_load16(ap[q], base + q * 1024);
+      direct_load16(bp[q], base + kLdsOperand + q * 1024);
+      ap[q] += a_step;
+      bp[q] += b_step;
+    }
+  };
+  uint4 fa[2][kIB], fb[2][kJB];
+  auto read_frags = [&](const char* stage, int ks, int f) {
+    const int ko = ks * 16 * kKmRowBytes;
+#pragma unroll
+    for (int i = 0; i < kIB; ++i) {
+      const uint2 lo = lds_read_tr16(stage + rd_a[i] + ko);
+      const uint2 hi = lds_read_tr16(stage + rd_a[i] + ko + 4 * kKmRowBytes);
+      fa[f][i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    }
+#pragma unroll
+    for (int j = 0; j < kJB; ++j) {
+      const uint2 lo = lds_read_tr16(stage + rd_b[j] + ko);
+      const uint2 hi = lds_read_tr16(stage + rd_b[j] + ko + 4 * kKmRowBytes);
+      fb[f][j] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    }
+  };
+  auto mfmas = [&](int f) {
+#pragma unroll
+    for (int i = 0; i < kIB; ++i)
+#pragma unroll
+      for (int j = 0; j < kJB; ++j) Mma<bf16_t>::run(fa[f][i], fb[f][j], acc[i][j]);
+  };
+
+  issue_loads(0);
+  if (nk > 1) issue_loads(1);
+  wait_direct_loads();
+  __syncthreads();
+  read_frags(smem, 0, 0);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cs = kt & 1;
+    const char* cur = smem + cs * kLdsStage;
+    const char* nxt = smem + (cs ^ 1) * kLdsStage;
+    read_frags(cur, 1, 1);
+    mfmas(0);
+    read_frags(cur, 2, 0);
+    mfmas(1);
+    read_frags(cur, 3, 1);
+    mfmas(0);
+    wait_direct_loads();
+    __syncthreads();
+    if (kt + 2 < nk) issue_loads(cs);
+    if (kt + 1 < nk) read_frags(nxt, 0, 0);
+    mfmas(1);
+  }
+}
+
 // Persistent-grid tile order.  Workgroups are dealt to the 8 XCDs round-robin by the hardware, so
 // workgroup w is given the logical slot (w % 8) * (grid / 8) + w / 8: the 32 workgroups that share
 // one XCD's L2 then walk neighbouring tiles.  Tiles are enumerated in bands of `band` A-tiles:

@@ -6,8 +6,10 @@
 // lse and logp.
 //
 // Backward: logits tiles are recomputed, turned into dZ = g (onehot - softmax) in registers and
-// written once in the element type of the inputs, in both orientations; two further
-// contractions give dHidden = dZ W and dW = dZ^T hidden.
+// written once, as dZ[token][vocab] in the element type of the inputs; two further contractions
+// give dHidden = dZ W (k = vocab, both operands contiguous along k) and dW = dZ^T hidden
+// (k = tokens, both operands read k-major through transposing LDS reads).  The fp32 path keeps a
+// second, transposed copy of dZ instead.
 #include "gemm_core.hpp"
 #include "head_kernels.hpp"
 
@@ -354,25 +356,6 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
                                     (static_cast<size_t>(t0 + row) * Vp + v0 + col16 * 8) * 2) = u;
         }
       }
-      // dZt[v][t]: the same staged tile read column-wise; a thread owns one vocabulary row and half
-      // of the tile's tokens, 8 tokens (16 bytes) per store
-      const int vrow = threadIdx.x & (kTile - 1);
-      const int thalf = (threadIdx.x >> 8) * (kTile / 2);
-      if (v0 + vrow < V) {
-        char* dst = reinterpret_cast<char*>(dZt) + (static_cast<size_t>(v0 + vrow) * TC + t0 + thalf) * 2;
-        const char* col = smem + thalf * kDzRowStride + vrow * 2;
-#pragma unroll 4
-        for (int tb = 0; tb < kTile / 16; ++tb) {
-          uint32_t w[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const uint32_t a = *reinterpret_cast<const uint16_t*>(col + (tb * 8 + 2 * e) * kDzRowStride);
-            const uint32_t b = *reinterpret_cast<const uint16_t*>(col + (tb * 8 + 2 * e + 1) * kDzRowStride);
-            w[e] = a | (b << 16);
-          }
-          *reinterpret_cast<uint4*>(dst + tb * 16) = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-      }
       __syncthreads();
     }
   }
@@ -477,6 +460,67 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dw(const T* __restrict__ 
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// hG[j][:] = hidden[idx[c0 + j]][:] for j < n, zero rows up to the next multiple of 256 (bf16 rows
+// of the super-chunk made contiguous so that the token contraction can stream them k-major)
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_gather_rows(const bf16_t* __restrict__ hidden,
+                                                     const int32_t* __restrict__ idx,
+                                                     const int32_t* __restrict__ cnt, int c0, int TC, int H,
+                                                     bf16_t* __restrict__ hG) {
+  const int n = chunk_count(cnt, c0, TC);
+  const int n_pad = (n + kTile - 1) / kTile * kTile;
+  const int chunks = H / 8;                       // 16-byte pieces per row
+  const int rows_per_block = 256 / 32;
+  for (int j = blockIdx.x * rows_per_block + (threadIdx.x >> 5); j < n_pad; j += gridDim.x * rows_per_block) {
+    const uint4* src = (j < n) ? reinterpret_cast<const uint4*>(hidden + static_cast<size_t>(idx[c0 + j]) * H) : nullptr;
+    uint4* dst = reinterpret_cast<uint4*>(hG + static_cast<size_t>(j) * H);
+    for (int c = threadIdx.x & 31; c < chunks; c += 32) dst[c] = src ? src[c] : make_uint4(0, 0, 0, 0);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dW (bf16): dW[v][h] (+)= sum_t dZ[t][v] * hG[t][h], both operands read k-major (no transposed
+// copies): A = dZ columns (vocab -> registers), B = hG columns (h -> lanes), k = tokens
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kGemmThreads) void k_head_dw_km(const bf16_t* __restrict__ dZ,
+                                                             const bf16_t* __restrict__ hG,
+                                                             const int32_t* __restrict__ cnt, int c0,
+                                                             float* __restrict__ dW, int H, int V, int Vp,
+                                                             int TC, int n_vtiles, int accumulate,
+                                                             int first_chunk) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int n = chunk_count(cnt, c0, TC);
+  if (n <= 0 && !(first_chunk && !accumulate)) return;
+  const TileOrder ord{n_vtiles, (H + kTile - 1) / kTile, 8};
+  const int total = ord.total();
+  const TileCoord tc;
+  const int nk = (n + kTile - 1) / kTile * kTile / kKmRows;
+
+  for (int t = logical_workgroup(); t < total; t += gridDim.x) {
+    int vt, ht;
+    ord.decode(t, &vt, &ht);
+    const int v0 = vt * kTile, h0 = ht * kTile;
+    floatx16 acc[kIB][kJB];
+    gemm_tile_kmajor(acc, reinterpret_cast<const char*>(dZ + v0), static_cast<size_t>(Vp) * 2,
+                     min(31, (Vp - v0) / 8 - 1), reinterpret_cast<const char*>(hG + h0),
+                     static_cast<size_t>(H) * 2, min(31, (H - h0) / 8 - 1), nk, smem);
+#pragma unroll
+    for (int i = 0; i < kIB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int v = v0 + tc.a_row(i, r);
+        if (v >= V) continue;
+        float* out = dW + static_cast<size_t>(v) * H;
+#pragma unroll
+        for (int jj = 0; jj < kJB; ++jj) {
+          const int h = h0 + tc.b_row(jj);
+          if (h < H) out[h] = accumulate ? out[h] + acc[i][jj][r] : acc[i][jj][r];
+        }
+      }
+  }
+}
+
 template <typename K>
 int allow_big_lds(K kernel, int bytes = kLdsBytes) {
   ATG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -542,15 +586,16 @@ int launch_transpose_w(const HeadGeom& g, const void* W, void* Wt, hipStream_t s
 int launch_gather_transpose_hidden(const HeadGeom& g, const HeadChunk& ch, const void* hidden, void* hT,
                                    hipStream_t s) {
   ProfScope ps(PROF_TRANSPOSE, s);
-  dim3 grid(static_cast<unsigned>(g.TC / 64), static_cast<unsigned>(ceil_div(g.H, 64)));
-  if (g.dtype == AT_GRPO_BF16)
-    hipLaunchKernelGGL(k_transpose<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t*>(hidden),
-                       static_cast<int64_t>(g.H), ch.idx, ch.cnt, ch.c0, g.TC, 0, 0, g.H,
-                       static_cast<bf16_t*>(hT), static_cast<int64_t>(g.TC));
-  else
+  if (g.dtype == AT_GRPO_BF16) {
+    // bf16: plain row gather (the token contraction reads it k-major)
+    hipLaunchKernelGGL(k_gather_rows, dim3(2048), dim3(256), 0, s, static_cast<const bf16_t*>(hidden), ch.idx,
+                       ch.cnt, ch.c0, g.TC, g.H, static_cast<bf16_t*>(hT));
+  } else {
+    dim3 grid(static_cast<unsigned>(g.TC / 64), static_cast<unsigned>(ceil_div(g.H, 64)));
     hipLaunchKernelGGL(k_transpose<float>, grid, dim3(256), 0, s, static_cast<const float*>(hidden),
                        static_cast<int64_t>(g.H), ch.idx, ch.cnt, ch.c0, g.TC, 0, 0, g.H,
                        static_cast<float*>(hT), static_cast<int64_t>(g.TC));
+  }
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }
@@ -599,15 +644,15 @@ int launch_head_dh(const HeadGeom& g, const HeadChunk& ch, const void* dZ, const
   return AT_GRPO_OK;
 }
 
-int launch_head_dw(const HeadGeom& g, const HeadChunk& ch, const void* dZt, const void* hT, float* dW,
-                   int accumulate, int first_chunk, hipStream_t s) {
+int launch_head_dw(const HeadGeom& g, const HeadChunk& ch, const void* dZ, const void* dZt, const void* hT,
+                   float* dW, int accumulate, int first_chunk, hipStream_t s) {
   ProfScope ps(PROF_HEAD_DW, s);
   if (g.dtype == AT_GRPO_BF16) {
-    auto k = k_head_dw<bf16_t>;
+    auto k = k_head_dw_km;
     ATG_TRY(allow_big_lds(k));
-    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
-                       static_cast<const bf16_t*>(dZt), static_cast<const bf16_t*>(hT), ch.cnt, ch.c0, dW,
-                       g.H, g.V, g.TC, g.n_vtiles, accumulate, first_chunk);
+    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s, static_cast<const bf16_t*>(dZ),
+                       static_cast<const bf16_t*>(hT), ch.cnt, ch.c0, dW, g.H, g.V, g.Vp, g.TC, g.n_vtiles,
+                       accumulate, first_chunk);
   } else {
     auto k = k_head_dw<float>;
     ATG_TRY(allow_big_lds(k));

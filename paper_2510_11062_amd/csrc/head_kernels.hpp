@@ -37,11 +37,12 @@ int launch_lse_combine(const HeadGeom& g, const HeadChunk& ch, const float* part
 // Wt[H][Vp] = W[V][H]^T, zero in the k padding.
 int launch_transpose_w(const HeadGeom& g, const void* W, void* Wt, hipStream_t s);
 
-// hT[H][TC] = (gathered hidden rows of this super-chunk)^T, zero for columns past the count.
+// fp32: hT[H][TC] = (gathered hidden rows of this super-chunk)^T, zero for columns past the count.
+// bf16: hT[TC][H] = the gathered rows themselves, zero rows up to the next multiple of 256.
 int launch_gather_transpose_hidden(const HeadGeom& g, const HeadChunk& ch, const void* hidden,
                                    void* hT, hipStream_t s);
 
-// dZ[TC][Vp] and dZt[V][TC] for this super-chunk (element type of hidden).
+// dZ[TC][Vp] for this super-chunk (element type of hidden); fp32 also fills dZt[V][TC].
 int launch_head_dz(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
                    const int32_t* token_id, const float* lse, const float* coef, void* dZ, void* dZt,
                    hipStream_t s);
@@ -50,8 +51,8 @@ int launch_head_dz(const HeadGeom& g, const HeadChunk& ch, const void* hidden, c
 int launch_head_dh(const HeadGeom& g, const HeadChunk& ch, const void* dZ, const void* Wt,
                    void* d_hidden, hipStream_t s);
 
-// dW[V][H] (+)= dZt . hT^T.  first_chunk: runs even for an empty list so that dW is defined.
-int launch_head_dw(const HeadGeom& g, const HeadChunk& ch, const void* dZt, const void* hT, float* dW,
-                   int accumulate, int first_chunk, hipStream_t s);
+// dW[V][H] (+)= dZ^T . hidden rows.  first_chunk: runs even for an empty list so that dW is defined.
+int launch_head_dw(const HeadGeom& g, const HeadChunk& ch, const void* dZ, const void* dZt, const void* hT,
+                   float* dW, int accumulate, int first_chunk, hipStream_t s);
 
 }  // namespace atg
