@@ -89,6 +89,14 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   return bf16_t{static_cast<uint16_t>(u >> 16)};
 }
 
+// two floats -> packed bf16 pair (low half = a), round to nearest even in hardware (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t f = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+}
+
 template <typename T>
 __device__ __forceinline__ T from_f32(float f);
 template <>

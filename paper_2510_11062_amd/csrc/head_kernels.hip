@@ -244,8 +244,8 @@ template <>
 struct Pack4<bf16_t> {
   static __device__ __forceinline__ void store(bf16_t* p, float a, float b, float c, float d) {
     uint2 u;
-    u.x = static_cast<uint32_t>(f32_to_bf16(a).bits) | (static_cast<uint32_t>(f32_to_bf16(b).bits) << 16);
-    u.y = static_cast<uint32_t>(f32_to_bf16(c).bits) | (static_cast<uint32_t>(f32_to_bf16(d).bits) << 16);
+    u.x = pack_bf16x2(a, b);
+    u.y = pack_bf16x2(c, d);
     *reinterpret_cast<uint2*>(p) = u;
   }
 };
@@ -325,8 +325,8 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
           }
           if (kStage) {
             uint2 u;
-            u.x = static_cast<uint32_t>(f32_to_bf16(d[0]).bits) | (static_cast<uint32_t>(f32_to_bf16(d[1]).bits) << 16);
-            u.y = static_cast<uint32_t>(f32_to_bf16(d[2]).bits) | (static_cast<uint32_t>(f32_to_bf16(d[3]).bits) << 16);
+            u.x = pack_bf16x2(d[0], d[1]);
+            u.y = pack_bf16x2(d[2], d[3]);
             *reinterpret_cast<uint2*>(smem + tc.b_row(j) * kDzRowStride + vl * 2) = u;
           } else {
             if (v < Vp) Pack4<T>::store(dZ + static_cast<size_t>(tcol[j]) * Vp + v, d[0], d[1], d[2], d[3]);
