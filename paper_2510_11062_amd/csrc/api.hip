@@ -119,7 +119,8 @@ void make_plan(const at_grpo_batch* b, int call, WsAlloc& ws, Plan* p) {
   S.blk_cnt = ws.take<int32_t>(static_cast<size_t>(M * S.n_blk));
   S.blk_off = ws.take<int32_t>(static_cast<size_t>(M * S.n_blk));
   S.resp_len = ws.take<int32_t>(static_cast<size_t>(b->n_resp));
-  S.blk_loss = ws.take<float>(static_cast<size_t>(M * S.n_blk256));
+  S.resp_sum = ws.take<float>(static_cast<size_t>(b->n_resp));
+  S.resp_head = ws.take<int32_t>(static_cast<size_t>(b->n_resp));
   const bool heads = call != AT_GRPO_CALL_SURROGATE;
   S.idx = heads ? ws.take<int32_t>(static_cast<size_t>(M) * static_cast<size_t>(n_tok)) : nullptr;
   if (!heads) return;
@@ -222,9 +223,7 @@ extern "C" int at_grpo_surrogate_from_logp(const at_grpo_batch* batch, const flo
   make_plan(batch, AT_GRPO_CALL_SURROGATE, ws, &p);
   ATG_TRY(check_workspace(workspace, workspace_bytes, ws.bytes()));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  ATG_TRY(launch_route(p.L, p.S, s));
-  ATG_TRY(launch_compact(p.L, p.S, false, s));
-  if (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN) ATG_TRY(launch_resp_len(p.L, p.S, s));
+  ATG_TRY(launch_fill_i32(p.S.err, 1, 0, s));
   return launch_surrogate(p.L, p.S, logp, old_logp, adv, eps_low, eps_high, agg, loss, clip_mask, n_valid, s);
 }
 
@@ -242,7 +241,6 @@ extern "C" int at_grpo_policy_loss_fwd(const at_grpo_batch* batch, const float* 
   ATG_TRY(check_workspace(workspace, workspace_bytes, ws.bytes()));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   ATG_TRY(enqueue_logprob(batch, p, logp, lse, s));
-  if (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN) ATG_TRY(launch_resp_len(p.L, p.S, s));
   return launch_surrogate(p.L, p.S, logp, old_logp, adv, eps_low, eps_high, agg, loss, clip_mask, n_valid, s);
 }
 

@@ -174,50 +174,144 @@ __device__ __forceinline__ float surrogate_term(float logp, float old_logp, floa
   return zero ? (high ? c.one_plus : c.one_minus) * A : r * A;
 }
 
-__global__ __launch_bounds__(256) void k_surrogate(int64_t n_tok, int n_heads,
-                                                   const int32_t* __restrict__ flag,
-                                                   const int32_t* __restrict__ resp_of_tok,
-                                                   const int32_t* __restrict__ resp_len,
-                                                   const float* __restrict__ logp,
-                                                   const float* __restrict__ old_logp,
-                                                   const float* __restrict__ adv, ClipConst cc, int agg,
-                                                   uint8_t* __restrict__ clip_mask, int64_t n_blk256,
-                                                   float* __restrict__ blk_loss) {
-  __shared__ float lds4[4];
-  const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-  int f = -1;
-  float term = 0.f;
-  if (t < n_tok) {
-    f = flag[t];
-    int bits = 0;
-    if (f >= 0) {
-      const int r = resp_of_tok[t];
-      float ratio;
-      term = surrogate_term(logp[t], old_logp[t], adv[r], cc, &bits, &ratio);
-      if (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN) term /= static_cast<float>(resp_len[r]);
+// One wavefront per response: every row of the response is read once (logp, old_logp, mask, and
+// token_id when given) in 4-row vectors, its clip flags are written, and the response's sum of
+// surrogate terms and its count of participating rows are reduced in a fixed order.  Needs no
+// per-row routing arrays: the advantage and the head are per-response scalars.
+__global__ __launch_bounds__(256) void k_surrogate_resp(TokenLayout L, const float* __restrict__ logp,
+                                                        const float* __restrict__ old_logp,
+                                                        const float* __restrict__ adv, ClipConst cc, int agg,
+                                                        uint8_t* __restrict__ clip_mask,
+                                                        float* __restrict__ resp_sum,
+                                                        int32_t* __restrict__ resp_cnt,
+                                                        int32_t* __restrict__ resp_head,
+                                                        int32_t* __restrict__ err) {
+  const int lane = threadIdx.x & 63;
+  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int n_waves = (gridDim.x * blockDim.x) >> 6;
+  for (int r = wave; r < L.n_resp; r += n_waves) {
+    const int64_t lo = L.cu_seqlens[r], hi = L.cu_seqlens[r + 1];
+    if (lo < 0 || hi < lo || hi > L.n_tok) {
+      if (lane == 0) {
+        atomicOr(err, AT_GRPO_DATA_SEQLENS);
+        resp_sum[r] = 0.f;
+        resp_cnt[r] = 0;
+        resp_head[r] = -1;
+      }
+      continue;
     }
-    if (clip_mask) clip_mask[t] = static_cast<uint8_t>(bits);
-  }
-  for (int m = 0; m < n_heads; ++m) {
-    const float tot = block_sum_256(f == m ? term : 0.f, lds4);
-    if (threadIdx.x == 0) blk_loss[m * n_blk256 + blockIdx.x] = tot;
+    const int head = head_of_response(r, L.n_heads, L.n_agent, L.resp_agent, L.head_of_agent, err);
+    const float A = adv[r];
+    float sum = 0.f;
+    int cnt = 0;
+    auto one = [&](int64_t t) {
+      bool on = (head >= 0) && (L.mask == nullptr || L.mask[t] != 0);
+      if (on && L.token_id != nullptr) {
+        const int y = L.token_id[t];
+        if (y < 0 || y >= L.V) {
+          atomicOr(err, AT_GRPO_DATA_TOKEN_RANGE);
+          on = false;
+        }
+      }
+      int bits = 0;
+      if (on) {
+        float ratio;
+        sum += surrogate_term(logp[t], old_logp[t], A, cc, &bits, &ratio);
+        ++cnt;
+      }
+      if (clip_mask) clip_mask[t] = static_cast<uint8_t>(bits);
+    };
+    for (int64_t u = (lo >> 2) + lane; (u << 2) < hi; u += 64) {
+      const int64_t t0 = u << 2;
+      if (t0 >= lo && t0 + 4 <= hi) {
+        const float4 lp = *reinterpret_cast<const float4*>(logp + t0);
+        const float4 ol = *reinterpret_cast<const float4*>(old_logp + t0);
+        uint32_t m4 = 0x01010101u;
+        if (L.mask) m4 = *reinterpret_cast<const uint32_t*>(L.mask + t0);
+        int4 y4 = make_int4(0, 0, 0, 0);
+        if (L.token_id) y4 = *reinterpret_cast<const int4*>(L.token_id + t0);
+        const float lpv[4] = {lp.x, lp.y, lp.z, lp.w};
+        const float olv[4] = {ol.x, ol.y, ol.z, ol.w};
+        const int yv[4] = {y4.x, y4.y, y4.z, y4.w};
+        uint32_t out = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          bool on = (head >= 0) && (((m4 >> (8 * e)) & 0xffu) != 0);
+          if (on && L.token_id != nullptr && (yv[e] < 0 || yv[e] >= L.V)) {
+            atomicOr(err, AT_GRPO_DATA_TOKEN_RANGE);
+            on = false;
+          }
+          if (on) {
+            int bits;
+            float ratio;
+            sum += surrogate_term(lpv[e], olv[e], A, cc, &bits, &ratio);
+            ++cnt;
+            out |= static_cast<uint32_t>(bits) << (8 * e);
+          }
+        }
+        if (clip_mask) *reinterpret_cast<uint32_t*>(clip_mask + t0) = out;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (t0 + e >= lo && t0 + e < hi) one(t0 + e);
+      }
+    }
+    // rows owned by no response (before the first / after the last range) carry no flags
+    if (clip_mask && r == 0)
+      for (int64_t t = lane; t < lo; t += 64) clip_mask[t] = 0;
+    if (clip_mask && r == L.n_resp - 1)
+      for (int64_t t = hi + lane; t < L.n_tok; t += 64) clip_mask[t] = 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      sum += __shfl_xor(sum, o, 64);
+      cnt += __shfl_xor(cnt, o, 64);
+    }
+    if (lane == 0) {
+      resp_sum[r] = (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN && cnt > 0) ? sum / static_cast<float>(cnt) : sum;
+      resp_cnt[r] = cnt;
+      resp_head[r] = head;
+    }
   }
 }
 
-// one block per head: fixed-order sum of the per-block partials
-__global__ __launch_bounds__(256) void k_loss_final(int64_t n_blk256, const float* __restrict__ blk_loss,
-                                                    const int32_t* __restrict__ cnt,
-                                                    const int32_t* __restrict__ resp_cnt, int agg,
-                                                    float* __restrict__ loss, int32_t* __restrict__ n_valid) {
-  __shared__ float lds4[4];
+// one 1024-thread block per head: fixed-order sums over the responses routed to it
+__global__ __launch_bounds__(1024) void k_loss_final(int n_resp, const float* __restrict__ resp_sum,
+                                                     const int32_t* __restrict__ resp_cnt,
+                                                     const int32_t* __restrict__ resp_head, int agg,
+                                                     float* __restrict__ loss, int32_t* __restrict__ n_valid) {
+  __shared__ float fs[16];
+  __shared__ int is[16], ir[16];
   const int m = blockIdx.x;
   float acc = 0.f;
-  for (int64_t b = threadIdx.x; b < n_blk256; b += 256) acc += blk_loss[m * n_blk256 + b];
-  const float tot = block_sum_256(acc, lds4);
+  int cnt = 0, nresp = 0;
+  for (int r = threadIdx.x; r < n_resp; r += 1024) {
+    if (resp_head[r] == m) {
+      acc += resp_sum[r];
+      cnt += resp_cnt[r];
+      nresp += (resp_cnt[r] > 0);
+    }
+  }
+  acc = wave_sum(acc);
+  cnt = wave_sum_int(cnt);
+  nresp = wave_sum_int(nresp);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) {
+    fs[wave] = acc;
+    is[wave] = cnt;
+    ir[wave] = nresp;
+  }
+  __syncthreads();
   if (threadIdx.x == 0) {
-    const int denom = (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN) ? resp_cnt[m] : cnt[m];
+    float tot = 0.f;
+    int c = 0, nr = 0;
+    for (int w = 0; w < 16; ++w) {
+      tot += fs[w];
+      c += is[w];
+      nr += ir[w];
+    }
+    const int denom = (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN) ? nr : c;
     loss[m] = denom > 0 ? -tot / static_cast<float>(denom) : 0.f;
-    if (n_valid) n_valid[m] = cnt[m];
+    if (n_valid) n_valid[m] = c;
   }
 }
 
@@ -343,12 +437,11 @@ int launch_surrogate(const TokenLayout& L, const TokenScratch& S, const float* l
                      uint8_t* clip_mask, int32_t* n_valid, hipStream_t s) {
   ProfScope ps(PROF_SURROGATE, s);
   const ClipConst cc = make_clip(eps_low, eps_high);
-  hipLaunchKernelGGL(k_surrogate, dim3(static_cast<unsigned>(S.n_blk256)), dim3(256), 0, s, L.n_tok,
-                     L.n_heads, S.flag, S.resp_of_tok, S.resp_len, logp, old_logp, adv, cc, agg, clip_mask,
-                     S.n_blk256, S.blk_loss);
+  hipLaunchKernelGGL(k_surrogate_resp, dim3(grid_for(L.n_resp, 4, 8192)), dim3(256), 0, s, L, logp, old_logp,
+                     adv, cc, agg, clip_mask, S.resp_sum, S.resp_len, S.resp_head, S.err);
   ATG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_loss_final, dim3(L.n_heads), dim3(256), 0, s, S.n_blk256, S.blk_loss, S.cnt,
-                     S.resp_cnt, agg, loss, n_valid);
+  hipLaunchKernelGGL(k_loss_final, dim3(L.n_heads), dim3(1024), 0, s, L.n_resp, S.resp_sum, S.resp_len,
+                     S.resp_head, agg, loss, n_valid);
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }

@@ -29,7 +29,8 @@ struct TokenScratch {
   int32_t* idx;          // [n_heads * n_tok] compacted rows per head
   int32_t* resp_len;     // [n_resp] participating rows per response
   int32_t* resp_cnt;     // [kMaxHeads] responses with at least one participating row, per head
-  float* blk_loss;       // [n_heads * n_blk256] per-block partial sums of the surrogate
+  float* resp_sum;       // [n_resp] per-response sum (or mean) of surrogate terms
+  int32_t* resp_head;    // [n_resp] head of each response (-1: takes no part)
   int64_t n_blk;         // ceil(n_tok / kTokPerBlock)
   int64_t n_blk256;      // ceil(n_tok / 256)
 };
@@ -46,7 +47,8 @@ int launch_compact(const TokenLayout& L, const TokenScratch& S, bool with_idx, h
 // resp_len / resp_cnt (only needed for the sequence-mean aggregation).
 int launch_resp_len(const TokenLayout& L, const TokenScratch& S, hipStream_t s);
 
-// Per-token surrogate terms + clip mask + per-head loss (Eq. 2).  Needs route + compact(cnt).
+// Per-token surrogate terms + clip mask + per-head loss (Eq. 2).  Self-contained: reads the layout
+// directly (one wavefront per response); overwrites resp_len with its own per-response counts.
 int launch_surrogate(const TokenLayout& L, const TokenScratch& S, const float* logp,
                      const float* old_logp, const float* adv, float eps_low, float eps_high, int agg,
                      float* loss, uint8_t* clip_mask, int32_t* n_valid, hipStream_t s);
