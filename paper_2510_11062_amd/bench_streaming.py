@@ -35,13 +35,13 @@ def _time(fn, iters=5, warmup=2):
     return (time.perf_counter() - t0) / iters
 
 
-def grouping(dev, E, N, T, K, label):
+def grouping(dev, E, N, T, K, label, shuffle=True):
     g = torch.Generator(device=dev)
     g.manual_seed(1234)
     R = E * N * T * K
     key = torch.arange(R, device=dev) // K
-    perm = torch.randperm(R, generator=g, device=dev)
-    key = key[perm]
+    if shuffle:
+        key = key[torch.randperm(R, generator=g, device=dev)]
     env = (key // (N * T)).to(torch.int32)
     agent = ((key // T) % N).to(torch.int32)
     turn = (key % T).to(torch.int32)
@@ -95,7 +95,9 @@ def main():
     out.append(grouping(dev, 16, 2, 4, 8, "C2 shape"))
     out.append(grouping(dev, 256, 2, 10, 4, "C4 shape"))
     out.append(grouping(dev, 64, 3, 4, 8, "C5 shape"))
-    out.append(grouping(dev, 262144, 2, 4, 8, "scaled twin of C2: 2^24 responses, K = 8"))
+    out.append(grouping(dev, 262144, 2, 4, 8, "scaled twin of C2: 2^24 responses, K = 8, shuffled order"))
+    out.append(grouping(dev, 262144, 2, 4, 8, "scaled twin of C2: 2^24 responses, K = 8, rollout order",
+                        shuffle=False))
     out.append(surrogate(dev, 6144, 290, "C5 row count (~1.8 M rows)"))
     out.append(surrogate(dev, 6144 * 16, 290, "16x twin of C5 (~28 M rows)"))
     for o in out:

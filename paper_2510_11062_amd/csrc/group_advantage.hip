@@ -5,9 +5,9 @@
 //   key = (e * n_agent + i) * n_turn + t,
 // groups are numbered densely in ascending key order, and the responses of a group are listed in
 // ascending original index (a stable sort by key).  Pipeline: histogram over the key space ->
-// exclusive scans (present keys -> dense ids, member counts -> CSR offsets) -> scatter through a
-// per-group cursor (arrival order is arbitrary) -> per-group ordering of the segment and the
-// fp32 statistics.  The final ordering makes every output deterministic.
+// exclusive scans (present keys -> dense ids, member counts -> CSR offsets) -> scatter by the
+// arrival rank the histogram's atomic returned (arbitrary order) -> per-group ordering of the
+// segment and the fp32 statistics.  The final ordering makes every output deterministic.
 #include "common.hpp"
 
 namespace atg {
@@ -31,19 +31,39 @@ __device__ __forceinline__ int64_t key_of(const GaArgs& a, int r, bool* ok) {
   return (static_cast<int64_t>(e) * a.n_agent + i) * a.n_turn + t;
 }
 
+// Histogram over the key box.  The atomic's return value is the response's arrival rank inside its
+// group.  Neighbouring lanes with the same key (candidates of one group emitted together, the
+// order a rollout produces) are folded into one atomic per run.
 __global__ __launch_bounds__(256) void k_ga_hist(GaArgs a, int32_t* __restrict__ err,
-                                                 int32_t* __restrict__ hist) {
+                                                 int32_t* __restrict__ hist, int32_t* __restrict__ key_of_resp,
+                                                 int32_t* __restrict__ rank_of_resp) {
   const int r = blockIdx.x * 256 + threadIdx.x;
-  if (r >= a.n_resp) return;
-  bool ok;
-  const int64_t key = key_of(a, r, &ok);
-  if (!ok) {
-    atomicOr(err, AT_GRPO_DATA_ID_RANGE);
-    return;
+  const int lane = threadIdx.x & 63;
+  int key = -1;
+  if (r < a.n_resp) {
+    bool ok;
+    const int64_t k64 = key_of(a, r, &ok);
+    if (ok) {
+      key = static_cast<int32_t>(k64);
+      const float x = a.reward[r];
+      if (!(fabsf(x) <= 3.402823466e38f)) atomicOr(err, AT_GRPO_DATA_REWARD);
+    } else {
+      atomicOr(err, AT_GRPO_DATA_ID_RANGE);
+    }
+    key_of_resp[r] = key;
   }
-  const float x = a.reward[r];
-  if (!(fabsf(x) <= 3.402823466e38f)) atomicOr(err, AT_GRPO_DATA_REWARD);
-  atomicAdd(&hist[key], 1);
+  // runs of equal keys inside the wavefront
+  const int prev = __shfl_up(key, 1, 64);
+  const bool head = (lane == 0) || (key != prev);
+  const unsigned long long heads = __builtin_amdgcn_ballot_w64(head);
+  const unsigned long long below = heads & ((2ull << lane) - 1ull);          // heads at or below this lane
+  const int start = 63 - __builtin_clzll(below);
+  const unsigned long long above = (lane == 63) ? 0ull : (heads >> (lane + 1)) << (lane + 1);
+  const int next = above ? __builtin_ctzll(above) : 64;
+  int base = 0;
+  if (head && key >= 0) base = atomicAdd(&hist[key], next - lane);
+  base = __shfl(base, start, 64);
+  if (r < a.n_resp && key >= 0) rank_of_resp[r] = base + (lane - start);
 }
 
 // per-block sums of (key present, members) over 2048 keys
@@ -94,13 +114,12 @@ __global__ __launch_bounds__(256) void k_ga_scan_top(int64_t n_blocks, int32_t* 
   }
 }
 
-// dense id of every present key, CSR offset and cleared cursor of every group
+// dense id of every present key and CSR offset of every group
 __global__ __launch_bounds__(256) void k_ga_scan_apply(const int32_t* __restrict__ hist, int64_t n_keys,
                                                        const int32_t* __restrict__ boff_p,
                                                        const int32_t* __restrict__ boff_c,
                                                        int32_t* __restrict__ gid_of_key,
-                                                       int32_t* __restrict__ seg_offsets,
-                                                       int32_t* __restrict__ cursor) {
+                                                       int32_t* __restrict__ seg_offsets) {
   __shared__ int lds4[4];
   const int64_t k0 = static_cast<int64_t>(blockIdx.x) * kKeysPerBlock + threadIdx.x * 8;
   int h[8];
@@ -119,32 +138,30 @@ __global__ __launch_bounds__(256) void k_ga_scan_apply(const int32_t* __restrict
     if (h[e] > 0) {
       gid_of_key[k0 + e] = gp;
       seg_offsets[gp] = gc;
-      cursor[gp] = 0;
       ++gp;
       gc += h[e];
     }
   }
 }
 
-__global__ __launch_bounds__(256) void k_ga_scatter(GaArgs a, const int32_t* __restrict__ gid_of_key,
+__global__ __launch_bounds__(256) void k_ga_scatter(int n_resp, const int32_t* __restrict__ key_of_resp,
+                                                    const int32_t* __restrict__ rank_of_resp,
+                                                    const int32_t* __restrict__ gid_of_key,
                                                     const int32_t* __restrict__ seg_offsets,
-                                                    int32_t* __restrict__ cursor,
                                                     int32_t* __restrict__ group_id,
                                                     int32_t* __restrict__ arrival,
                                                     float* __restrict__ adv) {
   const int r = blockIdx.x * 256 + threadIdx.x;
-  if (r >= a.n_resp) return;
-  bool ok;
-  const int64_t key = key_of(a, r, &ok);
-  if (!ok) {
+  if (r >= n_resp) return;
+  const int key = key_of_resp[r];
+  if (key < 0) {
     group_id[r] = -1;
     adv[r] = 0.f;
     return;
   }
   const int g = gid_of_key[key];
   group_id[r] = g;
-  const int pos = seg_offsets[g] + atomicAdd(&cursor[g], 1);
-  arrival[pos] = r;
+  arrival[seg_offsets[g] + rank_of_resp[r]] = r;
 }
 
 struct GaStat {
@@ -199,6 +216,59 @@ __global__ __launch_bounds__(256) void k_ga_finish_small(const int32_t* __restri
   for (int g = blockIdx.x * 256 + threadIdx.x; g < G; g += stride) {
     const int off = seg_offsets[g], n = seg_offsets[g + 1] - off;
     if (n > kSmallGroup) continue;
+    if (n <= 8) {
+      // whole group in registers: ranks by counting, sums taken in ascending-index order
+      int id[8];
+      float x[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) id[j] = (j < n) ? arrival[off + j] : 0x7fffffff;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) x[j] = (j < n) ? reward[id[j]] : 0.f;
+      int rank[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        int c = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) c += (id[i] < id[j]);
+        rank[j] = c;
+      }
+      float xs[8];      // rewards in perm order
+#pragma unroll
+      for (int pos = 0; pos < 8; ++pos) {
+        float v = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v = (rank[j] == pos && j < n) ? x[j] : v;
+        xs[pos] = v;
+      }
+      float sum = 0.f;
+      bool same = true;
+#pragma unroll
+      for (int pos = 0; pos < 8; ++pos)
+        if (pos < n) {
+          sum += xs[pos];
+          same = same && (xs[pos] == xs[0]);
+        }
+      float mean = same ? xs[0] : sum / static_cast<float>(n), sd = 0.f, ss = 0.f;
+#pragma unroll
+      for (int pos = 0; pos < 8; ++pos)
+        if (pos < n) {
+          const float d = xs[pos] - mean;
+          ss += d * d;
+        }
+      const int denom = n - st.ddof;
+      if (!same) sd = denom > 0 ? sqrtf(ss / static_cast<float>(denom)) : 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (j < n) {
+          perm[off + rank[j]] = id[j];
+          float a = 0.f;
+          if (!same) a = (st.norm == AT_GRPO_NORM_STD) ? (x[j] - mean) / (sd + st.eps_std) : (x[j] - mean);
+          adv[id[j]] = a;
+        }
+      if (group_mean) group_mean[g] = mean;
+      if (group_std) group_std[g] = sd;
+      continue;
+    }
     for (int j = 0; j < n; ++j) {
       const int rj = arrival[off + j];
       int rank = 0;
@@ -280,7 +350,7 @@ __global__ void k_ga_clear(int32_t* __restrict__ p, int64_t n) {
 
 struct GaPlan {
   int64_t n_keys, n_blocks;
-  int32_t *err, *hist, *gid_of_key, *cursor, *arrival, *bsum_p, *bsum_c;
+  int32_t *err, *hist, *gid_of_key, *key_of_resp, *rank_of_resp, *arrival, *bsum_p, *bsum_c;
 };
 
 bool plan(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn, WsAlloc& ws, GaPlan* p) {
@@ -292,7 +362,8 @@ bool plan(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn, WsAllo
   p->err = ws.take<int32_t>(64);
   p->hist = ws.take<int32_t>(static_cast<size_t>(n_keys));
   p->gid_of_key = ws.take<int32_t>(static_cast<size_t>(n_keys));
-  p->cursor = ws.take<int32_t>(static_cast<size_t>(n_resp < n_keys ? n_resp : n_keys) + 1);
+  p->key_of_resp = ws.take<int32_t>(static_cast<size_t>(n_resp));
+  p->rank_of_resp = ws.take<int32_t>(static_cast<size_t>(n_resp));
   p->arrival = ws.take<int32_t>(static_cast<size_t>(n_resp));
   p->bsum_p = ws.take<int32_t>(static_cast<size_t>(p->n_blocks));
   p->bsum_c = ws.take<int32_t>(static_cast<size_t>(p->n_blocks));
@@ -344,7 +415,7 @@ extern "C" int at_grpo_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_
   hipLaunchKernelGGL(k_ga_clear, dim3(static_cast<unsigned>(ceil_div(p.n_keys, 1024) > 4096 ? 4096 : ceil_div(p.n_keys, 1024))),
                      dim3(256), 0, s, p.hist, p.n_keys);
   ATG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_ga_hist, dim3(rb), dim3(256), 0, s, a, p.err, p.hist);
+  hipLaunchKernelGGL(k_ga_hist, dim3(rb), dim3(256), 0, s, a, p.err, p.hist, p.key_of_resp, p.rank_of_resp);
   ATG_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_ga_scan_partial, dim3(kb), dim3(256), 0, s, p.hist, p.n_keys, p.bsum_p, p.bsum_c);
   ATG_LAUNCH_CHECK();
@@ -352,10 +423,10 @@ extern "C" int at_grpo_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_
                      seg_offsets);
   ATG_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_ga_scan_apply, dim3(kb), dim3(256), 0, s, p.hist, p.n_keys, p.bsum_p, p.bsum_c,
-                     p.gid_of_key, seg_offsets, p.cursor);
+                     p.gid_of_key, seg_offsets);
   ATG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_ga_scatter, dim3(rb), dim3(256), 0, s, a, p.gid_of_key, seg_offsets, p.cursor,
-                     group_id, p.arrival, adv);
+  hipLaunchKernelGGL(k_ga_scatter, dim3(rb), dim3(256), 0, s, n_resp, p.key_of_resp, p.rank_of_resp,
+                     p.gid_of_key, seg_offsets, group_id, p.arrival, adv);
   ATG_LAUNCH_CHECK();
   // at most min(R, keys) groups exist; both finishing kernels stride over them
   const int64_t g_max = n_resp < p.n_keys ? n_resp : p.n_keys;

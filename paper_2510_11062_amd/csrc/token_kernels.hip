@@ -223,7 +223,8 @@ __global__ __launch_bounds__(256) void k_surrogate_resp(TokenLayout L, const flo
     };
     for (int64_t u = (lo >> 2) + lane; (u << 2) < hi; u += 64) {
       const int64_t t0 = u << 2;
-      if (t0 >= lo && t0 + 4 <= hi) {
+      if (t0 + 4 <= L.n_tok) {
+        // aligned 4-row vector; rows of a neighbouring response inside it are read but not used
         const float4 lp = *reinterpret_cast<const float4*>(logp + t0);
         const float4 ol = *reinterpret_cast<const float4*>(old_logp + t0);
         uint32_t m4 = 0x01010101u;
@@ -233,10 +234,12 @@ __global__ __launch_bounds__(256) void k_surrogate_resp(TokenLayout L, const flo
         const float lpv[4] = {lp.x, lp.y, lp.z, lp.w};
         const float olv[4] = {ol.x, ol.y, ol.z, ol.w};
         const int yv[4] = {y4.x, y4.y, y4.z, y4.w};
+        const bool interior = (t0 >= lo) && (t0 + 4 <= hi);
         uint32_t out = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          bool on = (head >= 0) && (((m4 >> (8 * e)) & 0xffu) != 0);
+          const bool mine = interior || (t0 + e >= lo && t0 + e < hi);
+          bool on = mine && (head >= 0) && (((m4 >> (8 * e)) & 0xffu) != 0);
           if (on && L.token_id != nullptr && (yv[e] < 0 || yv[e] >= L.V)) {
             atomicOr(err, AT_GRPO_DATA_TOKEN_RANGE);
             on = false;
@@ -249,7 +252,15 @@ __global__ __launch_bounds__(256) void k_surrogate_resp(TokenLayout L, const flo
             out |= static_cast<uint32_t>(bits) << (8 * e);
           }
         }
-        if (clip_mask) *reinterpret_cast<uint32_t*>(clip_mask + t0) = out;
+        if (clip_mask) {
+          if (interior) {
+            *reinterpret_cast<uint32_t*>(clip_mask + t0) = out;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (t0 + e >= lo && t0 + e < hi) clip_mask[t0 + e] = static_cast<uint8_t>(out >> (8 * e));
+          }
+        }
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -284,12 +295,14 @@ __global__ __launch_bounds__(1024) void k_loss_final(int n_resp, const float* __
   const int m = blockIdx.x;
   float acc = 0.f;
   int cnt = 0, nresp = 0;
+#pragma unroll 8
   for (int r = threadIdx.x; r < n_resp; r += 1024) {
-    if (resp_head[r] == m) {
-      acc += resp_sum[r];
-      cnt += resp_cnt[r];
-      nresp += (resp_cnt[r] > 0);
-    }
+    const bool mine = resp_head[r] == m;
+    const float sv = resp_sum[r];
+    const int cv = resp_cnt[r];
+    acc += mine ? sv : 0.f;
+    cnt += mine ? cv : 0;
+    nresp += (mine && cv > 0) ? 1 : 0;
   }
   acc = wave_sum(acc);
   cnt = wave_sum_int(cnt);
