@@ -25,6 +25,33 @@ if ROOT not in sys.path:
 from paper_2510_11062_amd import api, synth, workload  # noqa: E402
 
 PEAK = {"bf16": 2500.0, "f32": 157.3}      # dense MFMA TFLOP/s, MI355X data sheet
+CHUNK_TOKENS = 32768                       # list positions one head-kernel launch covers
+KERNEL_SYMBOL = {"head_fwd": "k_head_fwd", "head_dz": "k_head_dz", "head_dh": "k_head_dh", "head_dw": "k_head_dw"}
+
+
+def kernel_source_digest():
+    """sha256 over the HIP sources: HBM counter readings are only quoted for the code they were taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2510_11062_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".hpp")):
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()
+
+
+def recorded_traffic(workload_name, kern):
+    """HBM bytes per working launch of `kern` from the committed rocprofv3 --pmc summary, or None when
+    there is none for this workload/kernel or the kernels changed since it was taken."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload_name}.txt")
+    if not os.path.exists(path):
+        return None
+    rec = json.load(open(path))
+    if rec.get("source_digest") != kernel_source_digest():
+        return None
+    k = rec.get("kernels", {}).get(KERNEL_SYMBOL[kern])
+    return None if k is None else k["hbm_bytes_per_launch"]
+
 
 
 def cpu_baseline(cfg, st, batch, old_logp, n_sample):
@@ -60,6 +87,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="C2")
     ap.add_argument("--cpu-sample", type=int, default=256, help="response tokens given to the CPU oracle (0 = skip)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed steps, copy 1 GiB with torch (known traffic, to scale HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
@@ -110,11 +139,23 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     tokens_per_s = n_valid / (elapsed / args.steps)
 
+    if args.calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     hv2 = 2.0 * cfg.H * cfg.V
     flops = {"head_fwd": hv2 * n_valid, "head_dz": hv2 * n_grad, "head_dh": hv2 * n_grad, "head_dw": hv2 * n_grad}
     kern = max(flops, key=lambda k: prof[k][1])
     kern_ms = prof[kern][1] / args.steps
     achieved = flops[kern] / (kern_ms * 1e-3) / 1e12
+    # launches that had rows to process (the others return at once): per head, ceil(rows / chunk)
+    head_of_tok = wl.head_of_tok
+    live = valid if kern == "head_fwd" else (valid & (A_tok != 0) & ((fwd["clip_mask"] & 4) == 0))
+    rows_per_head = torch.bincount(head_of_tok[live], minlength=cfg.n_heads).tolist()
+    work_launches = sum(-(-r // CHUNK_TOKENS) for r in rows_per_head)
     peak = PEAK[cfg.dtype]
     all_gemm_ms = sum(prof[k][1] for k in flops) / args.steps
     all_gemm_tflops = sum(flops.values()) / (all_gemm_ms * 1e-3) / 1e12
@@ -130,7 +171,10 @@ def main():
                                f"{' (padded + mask)' if cfg.padded else ' (packed)'}",
                    "rows_with_gradient": n_grad, "device_error_word": err},
         "roofline": {"bound": "mfma", "kernel": kern, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None,
+                     "frac": achieved / peak, "traffic": recorded_traffic(cfg.name, kern),
+                     "flop_per_launch": flops[kern] / max(work_launches, 1),
+                     "ms_per_launch": kern_ms / max(work_launches, 1),
+                     "launches_with_rows_per_step": work_launches,
                      "kernel_ms_per_step": kern_ms, "launches_per_step": prof[kern][0] / args.steps,
                      "all_head_contractions_tflops": all_gemm_tflops,
                      "all_head_contractions_frac": all_gemm_tflops / peak},

@@ -183,17 +183,23 @@ __device__ __forceinline__ void gemm_tile(floatx16 (&acc)[kIB][kJB], AF a_row_pt
     const int cs = kt & 1;
     const char* cur = smem + cs * kLdsStage;
     const char* nxt = smem + (cs ^ 1) * kLdsStage;
+    // the scheduling fences keep each fragment prefetch ahead of the MFMAs it overlaps with
     read_frags(cur, 1, 1);
     mfmas(0);
+    __builtin_amdgcn_sched_barrier(0);
     read_frags(cur, 2, 0);
     mfmas(1);
+    __builtin_amdgcn_sched_barrier(0);
     read_frags(cur, 3, 1);
     mfmas(0);
+    __builtin_amdgcn_sched_barrier(0);
     wait_direct_loads();   // this wavefront's loads into `nxt` have landed
     __syncthreads();       // everyone's have, and everyone holds its last fragments of `cur`
+    __builtin_amdgcn_sched_barrier(0);
     if (kt + 2 < nk) issue_loads(cs);
     if (kt + 1 < nk) read_frags(nxt, 0, 0);
     mfmas(1);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -313,15 +319,20 @@ __device__ __forceinline__ void gemm_tile_kmajor(floatx16 (&acc)[kIB][kJB], cons
     const char* nxt = smem + (cs ^ 1) * kLdsStage;
     read_frags(cur, 1, 1);
     mfmas(0);
+    __builtin_amdgcn_sched_barrier(0);
     read_frags(cur, 2, 0);
     mfmas(1);
+    __builtin_amdgcn_sched_barrier(0);
     read_frags(cur, 3, 1);
     mfmas(0);
+    __builtin_amdgcn_sched_barrier(0);
     wait_direct_loads();
     __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
     if (kt + 2 < nk) issue_loads(cs);
     if (kt + 1 < nk) read_frags(nxt, 0, 0);
     mfmas(1);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 

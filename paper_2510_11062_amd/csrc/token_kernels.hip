@@ -174,10 +174,12 @@ __device__ __forceinline__ float surrogate_term(float logp, float old_logp, floa
   return zero ? (high ? c.one_plus : c.one_minus) * A : r * A;
 }
 
-// One wavefront per response: every row of the response is read once (logp, old_logp, mask, and
-// token_id when given) in 4-row vectors, its clip flags are written, and the response's sum of
-// surrogate terms and its count of participating rows are reduced in a fixed order.  Needs no
-// per-row routing arrays: the advantage and the head are per-response scalars.
+// LPR lanes per response (64, 32 or 16, chosen from the mean response length): every row of the
+// response is read once (logp, old_logp, mask, and token_id when given) in 4-row vectors, its clip
+// flags are written, and the response's sum of surrogate terms and its count of participating rows
+// are reduced in a fixed order.  Needs no per-row routing arrays: the advantage and the head are
+// per-response scalars.
+template <int LPR>
 __global__ __launch_bounds__(256) void k_surrogate_resp(TokenLayout L, const float* __restrict__ logp,
                                                         const float* __restrict__ old_logp,
                                                         const float* __restrict__ adv, ClipConst cc, int agg,
@@ -186,10 +188,10 @@ __global__ __launch_bounds__(256) void k_surrogate_resp(TokenLayout L, const flo
                                                         int32_t* __restrict__ resp_cnt,
                                                         int32_t* __restrict__ resp_head,
                                                         int32_t* __restrict__ err) {
-  const int lane = threadIdx.x & 63;
-  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  const int n_waves = (gridDim.x * blockDim.x) >> 6;
-  for (int r = wave; r < L.n_resp; r += n_waves) {
+  const int lane = threadIdx.x & (LPR - 1);
+  const int team = (blockIdx.x * blockDim.x + threadIdx.x) / LPR;
+  const int n_teams = (gridDim.x * blockDim.x) / LPR;
+  for (int r = team; r < L.n_resp; r += n_teams) {
     const int64_t lo = L.cu_seqlens[r], hi = L.cu_seqlens[r + 1];
     if (lo < 0 || hi < lo || hi > L.n_tok) {
       if (lane == 0) {
@@ -221,7 +223,7 @@ __global__ __launch_bounds__(256) void k_surrogate_resp(TokenLayout L, const flo
       }
       if (clip_mask) clip_mask[t] = static_cast<uint8_t>(bits);
     };
-    for (int64_t u = (lo >> 2) + lane; (u << 2) < hi; u += 64) {
+    for (int64_t u = (lo >> 2) + lane; (u << 2) < hi; u += LPR) {
       const int64_t t0 = u << 2;
       if (t0 + 4 <= L.n_tok) {
         // aligned 4-row vector; rows of a neighbouring response inside it are read but not used
@@ -269,11 +271,11 @@ __global__ __launch_bounds__(256) void k_surrogate_resp(TokenLayout L, const flo
     }
     // rows owned by no response (before the first / after the last range) carry no flags
     if (clip_mask && r == 0)
-      for (int64_t t = lane; t < lo; t += 64) clip_mask[t] = 0;
+      for (int64_t t = lane; t < lo; t += LPR) clip_mask[t] = 0;
     if (clip_mask && r == L.n_resp - 1)
-      for (int64_t t = hi + lane; t < L.n_tok; t += 64) clip_mask[t] = 0;
+      for (int64_t t = hi + lane; t < L.n_tok; t += LPR) clip_mask[t] = 0;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
+    for (int o = LPR / 2; o > 0; o >>= 1) {
       sum += __shfl_xor(sum, o, 64);
       cnt += __shfl_xor(cnt, o, 64);
     }
@@ -450,8 +452,16 @@ int launch_surrogate(const TokenLayout& L, const TokenScratch& S, const float* l
                      uint8_t* clip_mask, int32_t* n_valid, hipStream_t s) {
   ProfScope ps(PROF_SURROGATE, s);
   const ClipConst cc = make_clip(eps_low, eps_high);
-  hipLaunchKernelGGL(k_surrogate_resp, dim3(grid_for(L.n_resp, 4, 8192)), dim3(256), 0, s, L, logp, old_logp,
-                     adv, cc, agg, clip_mask, S.resp_sum, S.resp_len, S.resp_head, S.err);
+  const int64_t mean_rows = L.n_tok / (L.n_resp > 0 ? L.n_resp : 1);
+  if (mean_rows >= 512)
+    hipLaunchKernelGGL(k_surrogate_resp<64>, dim3(grid_for(L.n_resp, 4, 16384)), dim3(256), 0, s, L, logp,
+                       old_logp, adv, cc, agg, clip_mask, S.resp_sum, S.resp_len, S.resp_head, S.err);
+  else if (mean_rows >= 160)
+    hipLaunchKernelGGL(k_surrogate_resp<32>, dim3(grid_for(L.n_resp, 8, 16384)), dim3(256), 0, s, L, logp,
+                       old_logp, adv, cc, agg, clip_mask, S.resp_sum, S.resp_len, S.resp_head, S.err);
+  else
+    hipLaunchKernelGGL(k_surrogate_resp<16>, dim3(grid_for(L.n_resp, 16, 16384)), dim3(256), 0, s, L, logp,
+                       old_logp, adv, cc, agg, clip_mask, S.resp_sum, S.resp_len, S.resp_head, S.err);
   ATG_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_loss_final, dim3(L.n_heads), dim3(1024), 0, s, L.n_resp, S.resp_sum, S.resp_len,
                      S.resp_head, agg, loss, n_valid);
