@@ -86,7 +86,7 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="C2")
-    ap.add_argument("--cpu-sample", type=int, default=256, help="response tokens given to the CPU oracle (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=6144, help="response tokens given to the CPU oracle (0 = skip)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 1 GiB with torch (known traffic, to scale HBM counters)")
     args = ap.parse_args()

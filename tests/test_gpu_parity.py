@@ -372,3 +372,88 @@ def test_empty_head_and_all_masked_rows(gpu_device):
     assert float(fwd["logp"].abs().max()) == 0.0
     assert float(bwd["d_hidden"].abs().max()) == 0.0
     assert all(float(g.abs().max()) == 0.0 for g in bwd["dW"])
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,H,V", [("bf16", 192, 1001), ("f32", 96, 1001), ("bf16", 64, 130), ("bf16", 320, 8192)])
+@pytest.mark.parametrize("padded", [False, True])
+def test_odd_shapes_and_empty_responses(gpu_device, dtype, H, V, padded):
+    """Ragged everything: V not a multiple of the 64-wide k padding (or below one tile), H below one
+    tile, responses of length 0 and 1, row counts that are not multiples of 4, three heads."""
+    cfg = replace(synth.CONFIGS["C1"], name=f"odd-{dtype}-{H}-{V}", dtype=dtype, H=H, V=V, n_heads=3, E=5, N=3,
+                  T=2, K=3, len_lo=0, len_hi=9, padded=padded, reward_kind="uniform", forced_equal_groups=1,
+                  seed=synth.BASE_SEED + 77 + H)
+    tol = tolerances(cfg)
+    c = helpers.build_case(cfg, device=gpu_device)
+    assert (c.st.lengths == 0).any() and (c.st.lengths == 1).any()
+    c.old_logp = (c.old_logp + 2 * c.noise).astype(np.float32)
+    grad_loss = np.array([1.0, 0.25, 2.0])
+    for agg in ("token_mean", "seq_mean_token_mean"):
+        ref = helpers.oracle_bwd(c, agg=agg, grad_loss=grad_loss)
+        dc = DeviceCase(c, gpu_device)
+        say(f"[odd] {cfg.name} padded={padded} agg={agg}: rows={c.st.n_tok}")
+        fwd = api.at_grpo_policy_loss_fwd(dc.batch(), dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip, agg=agg)
+        gl = torch.from_numpy(grad_loss.astype(np.float32)).to(gpu_device)
+        bwd = api.at_grpo_policy_loss_bwd(dc.batch(), dc.old_logp, dc.adv, fwd["logp"], fwd["lse"], cfg.eps_clip,
+                                          cfg.eps_clip, agg=agg, grad_loss=gl)
+        torch.cuda.synchronize()
+        assert api.error_word(fwd["workspace"]) == 0
+        err = assert_logp_close(host(fwd["logp"]), ref["logp"], tol, "logp")
+        assert np.array_equal(host(fwd["n_valid"]), ref["n_valid"])
+        loss = host(fwd["loss"]).astype(np.float64)
+        assert np.all(np.abs(loss - ref["loss"]) <= tol["loss_rel"] * np.abs(ref["loss"]) + 1e-5), (loss, ref["loss"])
+        lo32, hi32 = orc.clip_thresholds(cfg.eps_clip, cfg.eps_clip)
+        d = ref["logp"].astype(np.float32) - c.old_logp
+        near = (np.abs(d - lo32) <= max(10 * err, 1e-6)) | (np.abs(d - hi32) <= max(10 * err, 1e-6))
+        assert not near.any()
+        assert np.array_equal(host(fwd["clip_mask"]), ref["clip_mask"])
+        assert helpers.rel_fro(host(bwd["d_hidden"]), ref["d_hidden"]) <= tol["grad_rel"]
+        assert np.all(host(bwd["d_hidden"])[ref["g"] == 0] == 0)
+        for k in range(3):
+            assert helpers.rel_fro(host(bwd["dW"][k]), ref["dW"][k]) <= tol["grad_rel"]
+
+
+@pytest.mark.gpu
+def test_single_row_batch(gpu_device):
+    cfg = replace(synth.CONFIGS["C1"], name="one-row", dtype="bf16", H=64, V=300, E=1, N=1, T=1, K=1, len_lo=1,
+                  len_hi=1, forced_equal_groups=0)
+    c = helpers.build_case(cfg, device=gpu_device)
+    c.adv = np.array([0.7], np.float32)            # a singleton group has advantage 0; give the row a gradient
+    ref = helpers.oracle_bwd(c)
+    dc = DeviceCase(c, gpu_device)
+    fwd = api.at_grpo_policy_loss_fwd(dc.batch(), dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip)
+    bwd = api.at_grpo_policy_loss_bwd(dc.batch(), dc.old_logp, dc.adv, fwd["logp"], fwd["lse"], cfg.eps_clip,
+                                      cfg.eps_clip)
+    torch.cuda.synchronize()
+    assert abs(float(fwd["logp"][0]) - ref["logp"][0]) <= 1e-2
+    assert abs(float(fwd["loss"][0]) - ref["loss"][0]) <= 2e-2 * abs(ref["loss"][0]) + 1e-5
+    assert helpers.rel_fro(host(bwd["d_hidden"]), ref["d_hidden"]) <= 2e-2
+    assert helpers.rel_fro(host(bwd["dW"][0]), ref["dW"][0]) <= 2e-2
+
+
+@pytest.mark.gpu
+def test_reproducible_and_independent_of_workspace_contents(gpu_device):
+    """No float atomics anywhere: two runs give identical bits, also when the scratch memory starts
+    out full of NaN patterns (every padded region the kernels read must be written by them first)."""
+    cfg = mini_cfg("C3")
+    c = helpers.build_case(cfg, device=gpu_device)
+    dc = DeviceCase(c, gpu_device)
+
+    def run():
+        ga = api.at_grpo_group_advantage(dc.env_id, dc.agent_id, dc.turn_id, dc.reward, cfg.E, cfg.N, cfg.T)
+        fwd = api.at_grpo_policy_loss_fwd(dc.batch(), dc.old_logp, ga["adv"], cfg.eps_clip, cfg.eps_clip)
+        bwd = api.at_grpo_policy_loss_bwd(dc.batch(), dc.old_logp, ga["adv"], fwd["logp"], fwd["lse"],
+                                          cfg.eps_clip, cfg.eps_clip)
+        torch.cuda.synchronize()
+        return [ga["adv"].clone(), ga["perm"].clone(), fwd["loss"].clone(), fwd["logp"].clone(), fwd["lse"].clone(),
+                fwd["clip_mask"].clone(), bwd["d_hidden"].clone()] + [g.clone() for g in bwd["dW"]]
+
+    say("[repro] first run")
+    first = run()
+    ws = api._workspace(1, gpu_device)
+    ws.fill_(0xFF)
+    say("[repro] second run on poisoned scratch")
+    second = run()
+    for a, b in zip(first, second):
+        assert torch.equal(a, b)
+    assert all(torch.isfinite(t.float()).all() for t in second)
