@@ -7,13 +7,22 @@
 // lane).  k is consumed in steps of 128 bytes per row (64 bf16 or 32 fp32 elements).
 //
 // Data path: global -> LDS with direct-to-LDS loads (global_load_lds_dwordx4, 16 bytes per lane,
-// one instruction fills 8 rows x 128 bytes), two LDS stages, loads issued one full k-step ahead;
-// LDS -> registers with ds_read_b128, fragments fetched one 16-wide sub-step ahead of the MFMAs
-// that consume them.  The 16-byte chunk index of every row is XOR-swizzled (applied on the global
-// side of the direct loads, since their LDS side is fixed to lane * 16) so that the fragment reads
-// are free of bank conflicts.  The direct loads are issued through inline asm: the compiler would
-// otherwise make every later LDS read wait for all outstanding direct loads.  Their completion is
-// enforced by hand with s_waitcnt vmcnt(0) in front of the one workgroup barrier per k-step.
+// one instruction fills 8 rows x 128 bytes), two LDS stages; LDS -> registers with ds_read_b128,
+// fragments fetched one 16-wide sub-step ahead of the MFMAs that consume them.  The 16-byte chunk
+// index of every row is XOR-swizzled (applied on the global side of the direct loads, since their
+// LDS side is fixed to lane * 16) so that the fragment reads are free of bank conflicts.  The direct
+// loads are issued through inline asm: the compiler would otherwise make every later LDS read wait
+// for all outstanding direct loads.  Their completion is enforced by hand with s_waitcnt vmcnt in
+// front of the one workgroup barrier per k-step.
+//
+// Instruction order: a wavefront that issues a burst of LDS reads or direct loads keeps its SIMD's
+// matrix pipe idle for the length of the burst (both wavefronts of a SIMD run in step, so the other
+// one rarely fills the gap).  The loop body is therefore written out as a fixed sequence, pinned with
+// scheduling barriers, in which every MFMA is followed by at most one LDS read and one direct load:
+// each memory instruction issues in the shadow of an MFMA that is already executing.  The 8 direct
+// loads a wavefront contributes to k-step kt+2 (stage kt & 1) are spread over the last sub-step of
+// step kt (3 loads, after the barrier that frees the stage) and the first two sub-steps of step
+// kt+1 (3 + 2); they must have landed at the barrier that ends sub-step 2 of step kt+1.
 //
 // Accumulator layout (per lane, block (i, j), register r = 0..15):
 //   a = wm*64 + i*32 + 8*(r/4) + 4*(lane/32) + (r%4)        (A row inside the tile)
@@ -34,6 +43,7 @@ constexpr int kGemmThreads = kWavesA * kWavesB * 64;
 constexpr int kIB = kTile / kWavesA / 32;        // 2 accumulator block rows per wavefront
 constexpr int kJB = kTile / kWavesB / 32;        // 4 accumulator block columns per wavefront
 constexpr int kLdsOperand = kTile * kStepBytes;  // 32 KiB
+constexpr int kLdOperandOffset = kLdsOperand;    // B follows A inside a stage
 constexpr int kLdsStage = 2 * kLdsOperand;       // A then B
 constexpr int kLdsBytes = 2 * kLdsStage;         // two stages: 128 KiB
 constexpr int kRowsPerWave = kTile / (kWavesA * kWavesB);   // operand rows each wavefront loads
@@ -97,6 +107,109 @@ __device__ __forceinline__ uint32_t lds_address(const char* p) {
 // s_waitcnt vmcnt(0) only (expcnt and lgkmcnt left at their maxima)
 __device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
+// Pinned k loop shared by both operand layouts.  Ops supplies
+//   mm(f, n)              MFMA group n (0..kIB*kJB-1) on fragment set f
+//   rd(stage, ks, f, n)   fetch of fragment n (0..kIB+kJB-1) of sub-step ks of `stage` into set f
+//   ld(stage, d)          direct load d (0..2*kLoadsPerWave-1) of the next k-step not yet requested
+// and the loop guarantees: loads of one k-step are requested in order d = 0, 1, ...; a stage is only
+// overwritten after the barrier that follows its last read; a workgroup barrier separates the last
+// LDS read from the return, so the caller may reuse the buffer at once.
+constexpr int kMmPerSub = kIB * kJB;              // 8
+constexpr int kRdPerSub = kIB + kJB;              // 6
+constexpr int kLdPerStep = 2 * kLoadsPerWave;     // 8
+constexpr int kLdSub3 = kLdPerStep * 3 / 8;       // requested in sub-step 3 of the step two ahead
+constexpr int kLdSub0 = kLdPerStep * 3 / 8;       // ... in sub-step 0 of the step before
+constexpr int kLdSub1 = kLdPerStep - kLdSub3 - kLdSub0;
+
+// index of the MFMA after which load k of `cnt` is issued within one sub-step
+__device__ __forceinline__ constexpr int load_slot(int k, int cnt) {
+  return (kMmPerSub - kRdPerSub >= cnt) ? kMmPerSub - cnt + k : ((k + 1) * kMmPerSub) / cnt - 1;
+}
+
+#define ATG_PIN() __builtin_amdgcn_sched_barrier(0)
+
+// One k-step.  HAS_NEXT: step kt+1 exists (its remaining loads are requested, its first fragments
+// fetched); HAS_NEXT2: step kt+2 exists (its first loads are requested).
+template <bool HAS_NEXT, bool HAS_NEXT2, typename Ops>
+__device__ __forceinline__ void pinned_k_step(Ops& ops, int kt, char* smem) {
+  const int cs = kt & 1;
+  const char* cur = smem + cs * kLdsStage;
+  const char* nxt = smem + (cs ^ 1) * kLdsStage;
+#pragma unroll
+  for (int ss = 0; ss < 3; ++ss) {
+    const int f = ss & 1;
+#pragma unroll
+    for (int n = 0; n < kMmPerSub; ++n) {
+      ops.mm(f, n);
+      ATG_PIN();
+      if (n < kRdPerSub) {
+        ops.rd(cur, ss + 1, f ^ 1, n);
+        ATG_PIN();
+      }
+      if (HAS_NEXT && ss == 0) {
+#pragma unroll
+        for (int k = 0; k < kLdSub0; ++k)
+          if (load_slot(k, kLdSub0) == n) {
+            ops.ld(cs ^ 1, kLdSub3 + k);
+            ATG_PIN();
+          }
+      }
+      if (HAS_NEXT && ss == 1) {
+#pragma unroll
+        for (int k = 0; k < kLdSub1; ++k)
+          if (load_slot(k, kLdSub1) == n) {
+            ops.ld(cs ^ 1, kLdSub3 + kLdSub0 + k);
+            ATG_PIN();
+          }
+      }
+    }
+  }
+  wait_direct_loads();   // this wavefront's loads into `nxt` have landed
+  __syncthreads();       // everyone's have, and everyone holds its last fragments of `cur`
+  ATG_PIN();
+#pragma unroll
+  for (int n = 0; n < kMmPerSub; ++n) {
+    ops.mm(1, n);
+    ATG_PIN();
+    if (HAS_NEXT && n < kRdPerSub) {
+      ops.rd(nxt, 0, 0, n);
+      ATG_PIN();
+    }
+    if (HAS_NEXT2) {
+#pragma unroll
+      for (int k = 0; k < kLdSub3; ++k)
+        if (load_slot(k, kLdSub3) == n) {
+          ops.ld(cs, k);
+          ATG_PIN();
+        }
+    }
+  }
+}
+
+template <typename Ops>
+__device__ __forceinline__ void pinned_k_loop(Ops& ops, int nk, char* smem) {
+  // prologue: all of step 0 and the first loads of step 1, which may still be in flight afterwards
+#pragma unroll
+  for (int d = 0; d < kLdPerStep; ++d) ops.ld(0, d);
+  if (nk > 1) {
+#pragma unroll
+    for (int d = 0; d < kLdSub3; ++d) ops.ld(1, d);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | kLdSub3);   // vmcnt(kLdSub3)
+  } else {
+    wait_direct_loads();
+  }
+  __syncthreads();
+#pragma unroll
+  for (int n = 0; n < kRdPerSub; ++n) ops.rd(smem, 0, 0, n);
+  int kt = 0;
+  for (; kt + 2 < nk; ++kt) pinned_k_step<true, true>(ops, kt, smem);
+  if (kt + 1 < nk) {
+    pinned_k_step<true, false>(ops, kt, smem);
+    ++kt;
+  }
+  pinned_k_step<false, false>(ops, kt, smem);
+}
+
 // Runs the k loop of one tile.  a_row_ptr(row) / b_row_ptr(row) return the global address of
 // k = 0 of tile row `row` (0..255); rows past the operand's end must be clamped by the functor
 // to some valid row (the epilogue masks them).  nk = number of 128-byte k steps (may be 0).
@@ -147,60 +260,37 @@ __device__ __forceinline__ void gemm_tile(floatx16 (&acc)[kIB][kJB], AF a_row_pt
   }
   const int half16 = (lane >> 5) << 4;
 
-  // each call fetches the next k-step into the given stage
-  auto issue_loads = [&](int stage) {
-    const uint32_t base = wave_lds + stage * kLdsStage;
-#pragma unroll
-    for (int q = 0; q < kLoadsPerWave; ++q) {
-      direct_load16(ap[q], base + q * 8 * kStepBytes);
-      direct_load16(bp[q], base + kLdsOperand + q * 8 * kStepBytes);
-      ap[q] += kStepBytes;
-      bp[q] += kStepBytes;
+  struct Ops {
+    floatx16 (&acc)[kIB][kJB];
+    const char* (&ap)[kLoadsPerWave];
+    const char* (&bp)[kLoadsPerWave];
+    const int (&rd_a)[kIB];
+    const int (&rd_b)[kJB];
+    const int (&sw_a)[kIB];
+    const int (&sw_b)[kJB];
+    uint32_t wave_lds;
+    int half16;
+    uint4 fa[2][kIB], fb[2][kJB];
+    __device__ __forceinline__ void mm(int f, int n) { Mma<T>::run(fa[f][n / kJB], fb[f][n % kJB], acc[n / kJB][n % kJB]); }
+    __device__ __forceinline__ void rd(const char* stage, int ks, int f, int n) {
+      const int cb = (ks << 5) | half16;
+      if (n < kIB) fa[f][n] = *reinterpret_cast<const uint4*>(stage + rd_a[n] + (cb ^ sw_a[n]));
+      else fb[f][n - kIB] = *reinterpret_cast<const uint4*>(stage + rd_b[n - kIB] + (cb ^ sw_b[n - kIB]));
+    }
+    __device__ __forceinline__ void ld(int stage, int d) {
+      const uint32_t base = wave_lds + stage * kLdsStage;
+      const int q = d >> 1;
+      if (d & 1) {
+        direct_load16(bp[q], base + kLdOperandOffset + q * 8 * kStepBytes);
+        bp[q] += kStepBytes;
+      } else {
+        direct_load16(ap[q], base + q * 8 * kStepBytes);
+        ap[q] += kStepBytes;
+      }
     }
   };
-  uint4 fa[2][kIB], fb[2][kJB];
-  auto read_frags = [&](const char* stage, int ks, int f) {
-    const int cb = (ks << 5) | half16;
-#pragma unroll
-    for (int i = 0; i < kIB; ++i) fa[f][i] = *reinterpret_cast<const uint4*>(stage + rd_a[i] + (cb ^ sw_a[i]));
-#pragma unroll
-    for (int j = 0; j < kJB; ++j) fb[f][j] = *reinterpret_cast<const uint4*>(stage + rd_b[j] + (cb ^ sw_b[j]));
-  };
-  auto mfmas = [&](int f) {
-#pragma unroll
-    for (int i = 0; i < kIB; ++i)
-#pragma unroll
-      for (int j = 0; j < kJB; ++j) Mma<T>::run(fa[f][i], fb[f][j], acc[i][j]);
-  };
-
-  issue_loads(0);
-  if (nk > 1) issue_loads(1);
-  wait_direct_loads();
-  __syncthreads();
-  read_frags(smem, 0, 0);
-
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cs = kt & 1;
-    const char* cur = smem + cs * kLdsStage;
-    const char* nxt = smem + (cs ^ 1) * kLdsStage;
-    // the scheduling fences keep each fragment prefetch ahead of the MFMAs it overlaps with
-    read_frags(cur, 1, 1);
-    mfmas(0);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(cur, 2, 0);
-    mfmas(1);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(cur, 3, 1);
-    mfmas(0);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_direct_loads();   // this wavefront's loads into `nxt` have landed
-    __syncthreads();       // everyone's have, and everyone holds its last fragments of `cur`
-    __builtin_amdgcn_sched_barrier(0);
-    if (kt + 2 < nk) issue_loads(cs);
-    if (kt + 1 < nk) read_frags(nxt, 0, 0);
-    mfmas(1);
-    __builtin_amdgcn_sched_barrier(0);
-  }
+  Ops ops{acc, ap, bp, rd_a, rd_b, sw_a, sw_b, wave_lds, half16, {}, {}};
+  pinned_k_loop(ops, nk, smem);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -274,66 +364,40 @@ __device__ __forceinline__ void gemm_tile_kmajor(floatx16 (&acc)[kIB][kJB], cons
     rd_b[j] = kLdsOperand + (8 * (g >> 1) + r) * kKmRowBytes + P * 16 + (m & 7) * 2;
   }
 
-  auto issue_loads = [&](int stage) {
-    const uint32_t base = wave_lds + stage * kLdsStage;
-#pragma unroll
-    for (int q = 0; q < kLoadsPerWave; ++q) {
-      direct_load16(ap[q], base + q * 1024);
-      direct_load16(bp[q], base + kLdsOperand + q * 1024);
-      ap[q] += a_step;
-      bp[q] += b_step;
+  struct Ops {
+    floatx16 (&acc)[kIB][kJB];
+    const char* (&ap)[kLoadsPerWave];
+    const char* (&bp)[kLoadsPerWave];
+    const int (&rd_a)[kIB];
+    const int (&rd_b)[kJB];
+    uint32_t wave_lds;
+    size_t a_step, b_step;
+    uint4 fa[2][kIB], fb[2][kJB];
+    __device__ __forceinline__ void mm(int f, int n) {
+      Mma<bf16_t>::run(fa[f][n / kJB], fb[f][n % kJB], acc[n / kJB][n % kJB]);
+    }
+    __device__ __forceinline__ void rd(const char* stage, int ks, int f, int n) {
+      const char* p = stage + ks * 16 * kKmRowBytes + (n < kIB ? rd_a[n % kIB] : rd_b[(n + kJB - kIB) % kJB]);
+      const uint2 lo = lds_read_tr16(p);
+      const uint2 hi = lds_read_tr16(p + 4 * kKmRowBytes);
+      const uint4 v = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      if (n < kIB) fa[f][n] = v;
+      else fb[f][n - kIB] = v;
+    }
+    __device__ __forceinline__ void ld(int stage, int d) {
+      const uint32_t base = wave_lds + stage * kLdsStage;
+      const int q = d >> 1;
+      if (d & 1) {
+        direct_load16(bp[q], base + kLdOperandOffset + q * 1024);
+        bp[q] += b_step;
+      } else {
+        direct_load16(ap[q], base + q * 1024);
+        ap[q] += a_step;
+      }
     }
   };
-  uint4 fa[2][kIB], fb[2][kJB];
-  auto read_frags = [&](const char* stage, int ks, int f) {
-    const int ko = ks * 16 * kKmRowBytes;
-#pragma unroll
-    for (int i = 0; i < kIB; ++i) {
-      const uint2 lo = lds_read_tr16(stage + rd_a[i] + ko);
-      const uint2 hi = lds_read_tr16(stage + rd_a[i] + ko + 4 * kKmRowBytes);
-      fa[f][i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
-    }
-#pragma unroll
-    for (int j = 0; j < kJB; ++j) {
-      const uint2 lo = lds_read_tr16(stage + rd_b[j] + ko);
-      const uint2 hi = lds_read_tr16(stage + rd_b[j] + ko + 4 * kKmRowBytes);
-      fb[f][j] = make_uint4(lo.x, lo.y, hi.x, hi.y);
-    }
-  };
-  auto mfmas = [&](int f) {
-#pragma unroll
-    for (int i = 0; i < kIB; ++i)
-#pragma unroll
-      for (int j = 0; j < kJB; ++j) Mma<bf16_t>::run(fa[f][i], fb[f][j], acc[i][j]);
-  };
-
-  issue_loads(0);
-  if (nk > 1) issue_loads(1);
-  wait_direct_loads();
-  __syncthreads();
-  read_frags(smem, 0, 0);
-
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cs = kt & 1;
-    const char* cur = smem + cs * kLdsStage;
-    const char* nxt = smem + (cs ^ 1) * kLdsStage;
-    read_frags(cur, 1, 1);
-    mfmas(0);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(cur, 2, 0);
-    mfmas(1);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(cur, 3, 1);
-    mfmas(0);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_direct_loads();
-    __syncthreads();
-    __builtin_amdgcn_sched_barrier(0);
-    if (kt + 2 < nk) issue_loads(cs);
-    if (kt + 1 < nk) read_frags(nxt, 0, 0);
-    mfmas(1);
-    __builtin_amdgcn_sched_barrier(0);
-  }
+  Ops ops{acc, ap, bp, rd_a, rd_b, wave_lds, a_step, b_step, {}, {}};
+  pinned_k_loop(ops, nk, smem);
 }
 
 // Persistent-grid tile order.  Workgroups are dealt to the 8 XCDs round-robin by the hardware, so
