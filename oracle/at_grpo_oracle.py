@@ -18,6 +18,10 @@ Paper passages followed (arXiv 2510.11062):
   * per-model batch B_m and clipped surrogate          -- Sec. 3, Eq. (2)
   * response-token credit (reward mask)                -- Sec. 4.1, first paragraph
   * pi_theta(token) from the LM head                   -- implicit in r(theta) below Eq. (2)
+  * mixed team / local reward                          -- Sec. 4.1 "Agent-wise Credit
+                                                        Assignment", Eq. (3)
+  * greedy choice of the executed candidate            -- Alg. 1 / Sec. 4.1 "Tree-structured
+                                                        Sampling"
 
 Readings taken where the paper is silent (all are parameters):
   * F_norm in Eq. (1) is the standard deviation; population (ddof=0) by default; the
@@ -108,6 +112,42 @@ def group_advantage(reward, group_id, n_groups: int, eps_std: float = 1e-6, ddof
         else:
             raise ValueError(norm)
     return adv, mean, std
+
+
+# --------------------------------------------------------------------------------------
+# Before S2: agent-wise credit assignment (Eq. 3) and the tree-sampling choice (Alg. 1)
+# --------------------------------------------------------------------------------------
+def mix_rewards(r_team, r_loc, alpha: float) -> np.ndarray:
+    """Eq. (3): r = alpha * r_team + r_loc, per candidate.
+
+    The result is the fp32 reward array that Eq. (1) consumes.  It decides integers further
+    down (which group counts as all-equal, which candidate is the arg max), so it is formed
+    in the precision the rewards live in: one fp32 multiplication, then one fp32 addition.
+    """
+    a = np.float32(alpha)
+    team = np.asarray(r_team, dtype=np.float32)
+    loc = np.asarray(r_loc, dtype=np.float32)
+    prod = (a * team).astype(np.float32)
+    return (prod + loc).astype(np.float32)
+
+
+def select_candidates(reward, group_id, n_groups: int) -> np.ndarray:
+    """Alg. 1, tree-structured sampling: c* = arg max_c r^(c) inside every group.
+
+    Returns best[G]: the response index of the candidate with the largest reward in each
+    group; among equal rewards the candidate that comes first (lowest response index).
+    """
+    r32 = np.asarray(reward, dtype=np.float32)
+    gid = np.asarray(group_id, dtype=np.int64)
+    best = np.full(n_groups, -1, dtype=np.int32)
+    for g in range(n_groups):
+        members = np.nonzero(gid == g)[0]          # ascending response index
+        top = members[0]
+        for m in members[1:]:
+            if r32[m] > r32[top]:
+                top = m
+        best[g] = top
+    return best
 
 
 # --------------------------------------------------------------------------------------

@@ -484,3 +484,72 @@ def test_config_c1_runs_and_is_self_consistent():
     # sampled tokens come from the softmax: mean logp is far above the uniform -ln V
     assert out["logp"].mean() > -math.log(512)
     assert abs(np.mean(out["logp"] - c.old_logp)) < 0.02
+
+
+# ----------------------------------------------------------------------------------------
+# Eq. (3) reward mixing and the tree-sampling choice of Alg. 1
+# ----------------------------------------------------------------------------------------
+def test_reward_mixing_exact_cases():
+    # dyadic values: every product and sum is exact, so the plain formula must come out exactly
+    team = np.array([0.0, 0.25, 0.5, 1.0, 0.75], dtype=np.float32)
+    loc = np.array([1.0, 0.5, 0.125, 0.0, 0.75], dtype=np.float32)
+    assert np.array_equal(orc.mix_rewards(team, loc, 1.0), np.array([1.0, 0.75, 0.625, 1.0, 1.5], np.float32))
+    assert np.array_equal(orc.mix_rewards(team, loc, 0.5), np.array([1.0, 0.625, 0.375, 0.5, 1.125], np.float32))
+    assert np.array_equal(orc.mix_rewards(team, loc, 0.0), loc)
+    assert np.array_equal(orc.mix_rewards(np.zeros(5, np.float32), loc, 3.0), loc)
+    # team and local rewards in [0, 1] with alpha = 1 land in [0, 2] (the paper's setting)
+    rng = np.random.default_rng(3)
+    r = orc.mix_rewards(rng.random(1000), rng.random(1000), 1.0)
+    assert r.dtype == np.float32 and r.min() >= 0.0 and r.max() <= 2.0
+
+
+def test_reward_mixing_against_exact_rationals():
+    from fractions import Fraction
+    rng = np.random.default_rng(11)
+    team = rng.random(200).astype(np.float32)
+    loc = (rng.random(200) * 3 - 1).astype(np.float32)
+    alpha = np.float32(0.3)
+    got = orc.mix_rewards(team, loc, alpha)
+    for k in range(200):
+        prod = Fraction(float(alpha)) * Fraction(float(team[k]))
+        exact = prod + Fraction(float(loc[k]))
+        # two fp32 roundings: of the product, then of the sum
+        bound = Fraction(2) ** -24 * (abs(prod) + abs(exact)) * Fraction(101, 100)
+        assert abs(Fraction(float(got[k])) - exact) <= bound, k
+
+
+def test_shared_team_reward_drops_out_of_the_advantage():
+    # Eq. (1) is shift invariant: if all candidates of a group see the same team reward, the
+    # advantages are those of the local rewards alone
+    rng = np.random.default_rng(5)
+    G, K = 12, 6
+    gid = np.repeat(np.arange(G), K)
+    loc = rng.integers(0, 9, size=G * K).astype(np.float32) / 8.0
+    team = np.repeat(rng.integers(0, 9, size=G).astype(np.float32) / 8.0, K)
+    mixed = orc.mix_rewards(team, loc, 1.0)
+    a_mixed, _, _ = orc.group_advantage(mixed, gid, G)
+    a_loc, _, _ = orc.group_advantage(loc, gid, G)
+    assert np.allclose(a_mixed, a_loc, rtol=0, atol=1e-12)
+
+
+def test_selection_matches_brute_force_and_tie_rule():
+    rng = np.random.default_rng(17)
+    R = 300
+    gid = rng.integers(0, 40, size=R)
+    present = np.unique(gid)
+    gid = np.searchsorted(present, gid)
+    G = present.shape[0]
+    reward = rng.integers(0, 3, size=R).astype(np.float32) / 2.0      # many ties
+    best = orc.select_candidates(reward, gid, G)
+    for g in range(G):
+        members = [r for r in range(R) if gid[r] == g]
+        want = max(members, key=lambda r: (float(reward[r]), -r))
+        assert best[g] == want
+        assert reward[best[g]] == max(reward[m] for m in members)
+        assert best[g] == min(m for m in members if reward[m] == reward[best[g]])
+    # scaling by a positive power of two changes no comparison
+    assert np.array_equal(orc.select_candidates(reward * 4.0, gid, G), best)
+    # singleton and all-equal groups pick their first member
+    gid2 = np.array([0, 1, 1, 1, 2, 2])
+    r2 = np.array([0.3, 0.5, 0.5, 0.5, 0.0, 1.0], dtype=np.float32)
+    assert orc.select_candidates(r2, gid2, 3).tolist() == [0, 1, 5]
