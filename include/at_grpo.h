@@ -125,6 +125,27 @@ int at_grpo_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int3
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The same with the step in front of it: agent-wise credit assignment, Eq. (3) of Sec. 4.1,
+ *   reward[r] = alpha * r_team[r] + r_loc[r]     (one fp32 multiplication, then one fp32 addition)
+ * feeds Eq. (1), and the greedy choice of tree-structured sampling (Alg. 1, "c* <- arg max_c r^(c)")
+ * is taken on the same groups:
+ *   reward[R]   output, the mixed reward (also what adv, group_mean, group_std are computed from)
+ *   best[G]     optional (NULL to skip): response index of the candidate with the largest reward of
+ *               each group, the lowest response index among equal rewards; the buffer must hold
+ *               min(R, n_env*n_agent*n_turn) entries
+ * r_team[R], r_loc[R] are inputs; alpha must be finite.  Every other argument, the workspace size
+ * (AT_GRPO_CALL_GROUP_ADVANTAGE) and the error behaviour are those of at_grpo_group_advantage; a
+ * non-finite mixed reward raises AT_GRPO_DATA_REWARD.
+ */
+int at_grpo_group_advantage_mixed(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn,
+                                  const int32_t* env_id, const int32_t* agent_id, const int32_t* turn_id,
+                                  const float* r_team, const float* r_loc, float alpha, float eps_std,
+                                  int32_t ddof, int32_t norm, float* reward, int32_t* group_id,
+                                  int32_t* n_groups, int32_t* seg_offsets, int32_t* perm, float* adv,
+                                  float* group_mean, float* group_std, int32_t* best, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream);
+
+/*
  * log pi_theta(token_id[t]) and the log-sum-exp of the head logits for every participating row
  * (the policy probability inside r(theta) below Eq. 2).  Logits z[t, v] = <hidden[t], W_m[v]>
  * are produced tile by tile on the matrix cores and reduced on the fly; they are never written

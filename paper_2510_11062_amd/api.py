@@ -22,7 +22,7 @@ NORM = {"std": 0, "none": 1}
 CALL_GROUP_ADVANTAGE, CALL_TOKEN_LOGPROB, CALL_POLICY_LOSS_FWD, CALL_POLICY_LOSS_BWD, CALL_SURROGATE = range(5)
 
 EXPORTS = [
-    "at_grpo_group_advantage", "at_grpo_token_logprob", "at_grpo_surrogate_from_logp",
+    "at_grpo_group_advantage", "at_grpo_group_advantage_mixed", "at_grpo_token_logprob", "at_grpo_surrogate_from_logp",
     "at_grpo_policy_loss_fwd", "at_grpo_policy_loss_bwd", "at_grpo_workspace_bytes",
     "at_grpo_status_string", "at_grpo_version", "at_grpo_profile_enable", "at_grpo_profile_classes",
     "at_grpo_profile_read",
@@ -60,6 +60,9 @@ def load_library():
     lib.at_grpo_group_advantage.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, f32, i32, i32,
                                             vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.at_grpo_group_advantage.restype = C.c_int
+    lib.at_grpo_group_advantage_mixed.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, f32, f32, i32, i32,
+                                                  vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.at_grpo_group_advantage_mixed.restype = C.c_int
     lib.at_grpo_token_logprob.argtypes = [C.POINTER(_Batch), vp, vp, vp, sz, vp]
     lib.at_grpo_token_logprob.restype = C.c_int
     lib.at_grpo_surrogate_from_logp.argtypes = [C.POINTER(_Batch), vp, vp, vp, f32, f32, i32, vp, vp, vp,
@@ -212,6 +215,44 @@ def at_grpo_group_advantage(env_id, agent_id, turn_id, reward, n_env: int, n_age
                                      _ptr(out["adv"]), _ptr(out["group_mean"]), _ptr(out["group_std"]),
                                      _ptr(ws), ws.numel(), _stream())
     _check(st, "at_grpo_group_advantage")
+    out["workspace"] = ws
+    return out
+
+
+def at_grpo_group_advantage_mixed(env_id, agent_id, turn_id, r_team, r_loc, alpha: float, n_env: int,
+                                  n_agent: int, n_turn: int, eps_std: float = 1e-6, ddof: int = 0,
+                                  norm: str = "std", want_stats: bool = True, want_best: bool = True):
+    """Eq. (3) mixing in front of at_grpo_group_advantage, plus the per-group arg max.
+
+    Returns the dict of at_grpo_group_advantage extended by reward[R] and best[min(R, keys)]."""
+    lib = load_library()
+    _dev_check(env_id, agent_id, turn_id, r_team, r_loc)
+    dev = r_team.device
+    R = r_team.numel()
+    n_keys = n_env * n_agent * n_turn
+    gmax = min(R, n_keys)
+    out = dict(
+        reward=torch.empty(R, dtype=torch.float32, device=dev),
+        group_id=torch.empty(R, dtype=torch.int32, device=dev),
+        n_groups=torch.zeros(1, dtype=torch.int32, device=dev),
+        seg_offsets=torch.zeros(gmax + 1, dtype=torch.int32, device=dev),
+        perm=torch.zeros(R, dtype=torch.int32, device=dev),
+        adv=torch.empty(R, dtype=torch.float32, device=dev),
+        group_mean=torch.zeros(gmax, dtype=torch.float32, device=dev) if want_stats else None,
+        group_std=torch.zeros(gmax, dtype=torch.float32, device=dev) if want_stats else None,
+        best=torch.full((gmax,), -1, dtype=torch.int32, device=dev) if want_best else None,
+    )
+    nbytes = lib.at_grpo_workspace_bytes(CALL_GROUP_ADVANTAGE, None, R, n_env, n_agent, n_turn)
+    if nbytes == 0:
+        raise AtGrpoError("at_grpo_workspace_bytes rejected the id extents")
+    ws = _workspace(nbytes, dev)
+    st = lib.at_grpo_group_advantage_mixed(R, n_env, n_agent, n_turn, _ptr(env_id), _ptr(agent_id),
+                                           _ptr(turn_id), _ptr(r_team), _ptr(r_loc), alpha, eps_std, ddof,
+                                           NORM[norm], _ptr(out["reward"]), _ptr(out["group_id"]),
+                                           _ptr(out["n_groups"]), _ptr(out["seg_offsets"]), _ptr(out["perm"]),
+                                           _ptr(out["adv"]), _ptr(out["group_mean"]), _ptr(out["group_std"]),
+                                           _ptr(out["best"]), _ptr(ws), ws.numel(), _stream())
+    _check(st, "at_grpo_group_advantage_mixed")
     out["workspace"] = ws
     return out
 

@@ -343,6 +343,45 @@ __global__ __launch_bounds__(256) void k_ga_finish_large(const int32_t* __restri
   }
 }
 
+// Eq. (3): r = alpha * r_team + r_loc.  One fp32 multiplication, then one fp32 addition (never
+// contracted to an fma): the result decides which groups count as all-equal and which candidate
+// is the arg max, so its rounding is part of the definition.
+__global__ __launch_bounds__(256) void k_ga_mix(int n, const float* __restrict__ r_team,
+                                                const float* __restrict__ r_loc, float alpha,
+                                                float* __restrict__ reward) {
+#pragma clang fp contract(off)
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r < n) {
+    const float prod = alpha * r_team[r];
+    reward[r] = prod + r_loc[r];
+  }
+}
+
+// Tree-structured sampling (Alg. 1): c* = arg max_c r^(c) per group, the first of equal rewards.
+// perm lists a group's members in ascending response index, so a strict comparison keeps the first.
+__global__ __launch_bounds__(256) void k_ga_select(const int32_t* __restrict__ n_groups,
+                                                   const int32_t* __restrict__ seg_offsets,
+                                                   const int32_t* __restrict__ perm,
+                                                   const float* __restrict__ reward,
+                                                   int32_t* __restrict__ best) {
+  const int G = *n_groups;
+  const int stride = gridDim.x * 256;
+  for (int g = blockIdx.x * 256 + threadIdx.x; g < G; g += stride) {
+    const int off = seg_offsets[g], n = seg_offsets[g + 1] - off;
+    int top = perm[off];
+    float xt = reward[top];
+    for (int j = 1; j < n; ++j) {
+      const int r = perm[off + j];
+      const float x = reward[r];
+      if (x > xt) {
+        xt = x;
+        top = r;
+      }
+    }
+    best[g] = top;
+  }
+}
+
 __global__ void k_ga_clear(int32_t* __restrict__ p, int64_t n) {
   const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
   for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0;
@@ -383,14 +422,16 @@ size_t group_advantage_workspace(int32_t n_resp, int32_t n_env, int32_t n_agent,
 
 using namespace atg;
 
-extern "C" int at_grpo_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn,
-                                       const int32_t* env_id, const int32_t* agent_id,
-                                       const int32_t* turn_id, const float* reward, float eps_std,
-                                       int32_t ddof, int32_t norm, int32_t* group_id, int32_t* n_groups,
-                                       int32_t* seg_offsets, int32_t* perm, float* adv, float* group_mean,
-                                       float* group_std, void* workspace, size_t workspace_bytes,
-                                       void* hip_stream) {
-  if (!env_id || !agent_id || !turn_id || !reward || !group_id || !n_groups || !seg_offsets || !perm || !adv)
+namespace {
+
+int run_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn,
+                        const int32_t* env_id, const int32_t* agent_id, const int32_t* turn_id,
+                        const float* reward, float eps_std, int32_t ddof, int32_t norm, int32_t* group_id,
+                        int32_t* n_groups, int32_t* seg_offsets, int32_t* perm, float* adv,
+                        float* group_mean, float* group_std, const float* r_team, const float* r_loc,
+                        float alpha, float* reward_out, int32_t* best, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  if (!env_id || !agent_id || !turn_id || !group_id || !n_groups || !seg_offsets || !perm || !adv)
     return AT_GRPO_EINVAL;
   if (n_resp <= 0 || n_env <= 0 || n_agent <= 0 || n_turn <= 0) return AT_GRPO_EINVAL;
   if (ddof != 0 && ddof != 1) return AT_GRPO_EINVAL;
@@ -404,6 +445,13 @@ extern "C" int at_grpo_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   ProfScope ps(PROF_GROUP, s);
 
+  if (r_team) {
+    // the mixed reward is an output; everything below reads it
+    hipLaunchKernelGGL(k_ga_mix, dim3(static_cast<unsigned>(ceil_div(n_resp, 256))), dim3(256), 0, s, n_resp,
+                       r_team, r_loc, alpha, reward_out);
+    ATG_LAUNCH_CHECK();
+    reward = reward_out;
+  }
   const GaArgs a{n_resp, n_env, n_agent, n_turn, env_id, agent_id, turn_id, reward};
   const GaStat st{eps_std, ddof, norm};
   const unsigned rb = static_cast<unsigned>(ceil_div(n_resp, 256));
@@ -438,5 +486,41 @@ extern "C" int at_grpo_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_
   hipLaunchKernelGGL(k_ga_finish_large, dim3(fl), dim3(256), 0, s, n_groups, seg_offsets, p.arrival, reward,
                      st, perm, adv, group_mean, group_std);
   ATG_LAUNCH_CHECK();
+  if (best) {
+    hipLaunchKernelGGL(k_ga_select, dim3(fs), dim3(256), 0, s, n_groups, seg_offsets, perm, reward, best);
+    ATG_LAUNCH_CHECK();
+  }
   return AT_GRPO_OK;
 }
+
+}  // namespace
+
+extern "C" int at_grpo_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn,
+                                       const int32_t* env_id, const int32_t* agent_id,
+                                       const int32_t* turn_id, const float* reward, float eps_std,
+                                       int32_t ddof, int32_t norm, int32_t* group_id, int32_t* n_groups,
+                                       int32_t* seg_offsets, int32_t* perm, float* adv, float* group_mean,
+                                       float* group_std, void* workspace, size_t workspace_bytes,
+                                       void* hip_stream) {
+  if (!reward) return AT_GRPO_EINVAL;
+  return run_group_advantage(n_resp, n_env, n_agent, n_turn, env_id, agent_id, turn_id, reward, eps_std, ddof,
+                             norm, group_id, n_groups, seg_offsets, perm, adv, group_mean, group_std, nullptr,
+                             nullptr, 0.f, nullptr, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int at_grpo_group_advantage_mixed(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn,
+                                             const int32_t* env_id, const int32_t* agent_id,
+                                             const int32_t* turn_id, const float* r_team,
+                                             const float* r_loc, float alpha, float eps_std, int32_t ddof,
+                                             int32_t norm, float* reward, int32_t* group_id,
+                                             int32_t* n_groups, int32_t* seg_offsets, int32_t* perm,
+                                             float* adv, float* group_mean, float* group_std,
+                                             int32_t* best, void* workspace, size_t workspace_bytes,
+                                             void* hip_stream) {
+  if (!r_team || !r_loc || !reward) return AT_GRPO_EINVAL;
+  if (!(fabsf(alpha) <= 3.402823466e38f)) return AT_GRPO_EINVAL;
+  return run_group_advantage(n_resp, n_env, n_agent, n_turn, env_id, agent_id, turn_id, reward, eps_std, ddof,
+                             norm, group_id, n_groups, seg_offsets, perm, adv, group_mean, group_std, r_team,
+                             r_loc, alpha, reward, best, workspace, workspace_bytes, hip_stream);
+}
+

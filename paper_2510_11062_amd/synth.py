@@ -156,6 +156,16 @@ def make_structure(cfg: RolloutConfig) -> RolloutStructure:
                             n_tok, int(lengths.sum()))
 
 
+def make_team_local_rewards(cfg: RolloutConfig, n_resp: int, levels: int = 8):
+    """Team and local reward of every candidate, as a coder/tester-style workflow produces them:
+    pass rates over `levels` unit tests, i.e. multiples of 1/levels in [0, 1] (so equal rewards are
+    common).  Returns (r_team[R], r_loc[R]) as fp32; no arithmetic of the method happens here."""
+    rng = np.random.default_rng(cfg.seed * 7 + 3)
+    r_team = rng.integers(0, levels + 1, size=n_resp).astype(np.float32) / np.float32(levels)
+    r_loc = rng.integers(0, levels + 1, size=n_resp).astype(np.float32) / np.float32(levels)
+    return r_team, r_loc
+
+
 def torch_dtype(cfg: RolloutConfig):
     return torch.float32 if cfg.dtype == "f32" else torch.bfloat16
 

@@ -60,6 +60,9 @@ def test_workspace_query_and_argument_errors_on_host():
     st = lib.at_grpo_group_advantage(4, 1, 1, 1, None, None, None, None, 1e-6, 0, 0,
                                      None, None, None, None, None, None, None, None, 0, None)
     assert st == 1
+    st = lib.at_grpo_group_advantage_mixed(4, 1, 1, 1, None, None, None, None, None, 1.0, 1e-6, 0, 0, None,
+                                           None, None, None, None, None, None, None, None, None, 0, None)
+    assert st == 1
     b.H = 2048
     assert lib.at_grpo_token_logprob(b, None, None, None, 0, None) == 1
 
@@ -83,7 +86,7 @@ def check_group_advantage(out, st, cfg, eps_std=1e-6, ddof=0, norm="std"):
     assert np.array_equal(host(out["seg_offsets"])[:G + 1], offs)
     assert np.array_equal(host(out["perm"]), perm)
     got = host(out["adv"]).astype(np.float64)
-    assert np.all(got[adv == 0] == 0)                        # degenerate groups: exactly zero
+    assert np.all(got[std[gid] == 0] == 0)                   # all-equal groups: exactly zero
     assert np.allclose(got, adv, rtol=1e-4, atol=1e-6)
     assert np.allclose(host(out["group_mean"])[:G], mean, rtol=1e-4, atol=1e-7)
     assert np.allclose(host(out["group_std"])[:G], std, rtol=1e-4, atol=1e-7)
@@ -140,6 +143,55 @@ def test_group_advantage_mixed_group_sizes_and_determinism(gpu_device):
     again = run_group_advantage(gpu_device, st, cfg)
     for k in ("group_id", "seg_offsets", "perm", "adv", "group_mean", "group_std"):
         assert torch.equal(first[k], again[k])
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,alpha", [("C1", 1.0), ("C2", 1.0), ("C3", 0.3), ("C4", 1.0), ("C5", 0.7)])
+def test_group_advantage_mixed_matches_oracle(gpu_device, name, alpha):
+    """Eq. (3) mixing + Eq. (1) + the tree-sampling arg max, at the configurations' real R."""
+    cfg = synth.CONFIGS[name]
+    st = synth.make_structure(cfg)
+    r_team, r_loc = synth.make_team_local_rewards(cfg, cfg.n_resp)
+    if name == "C3":
+        r_loc = (r_loc * np.float32(1.7) + np.float32(0.1)).astype(np.float32)   # inexact products and sums
+    say(f"[group_advantage_mixed] {name} R={cfg.n_resp} alpha={alpha}")
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(gpu_device)
+    f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(gpu_device)
+    out = api.at_grpo_group_advantage_mixed(i32(st.env_id), i32(st.agent_id), i32(st.turn_id), f32(r_team),
+                                            f32(r_loc), alpha, cfg.E, cfg.N, cfg.T)
+    torch.cuda.synchronize()
+    assert api.error_word(out["workspace"]) == 0
+    mixed = orc.mix_rewards(r_team, r_loc, alpha)
+    assert np.array_equal(host(out["reward"]).view(np.uint32), mixed.view(np.uint32))    # bit-exact
+    st.reward = mixed
+    check_group_advantage(out, st, cfg)
+    key = orc.group_key(st.env_id, st.agent_id, st.turn_id, cfg.N, cfg.T)
+    gid, G, _, _ = orc.group_segments(key)
+    assert np.array_equal(host(out["best"])[:G], orc.select_candidates(mixed, gid, G))
+
+
+@pytest.mark.gpu
+def test_group_advantage_mixed_large_groups_and_no_best(gpu_device):
+    cfg = replace(synth.CONFIGS["C4"], E=3, N=1, T=2, K=700)
+    st = synth.make_structure(cfg)
+    r_team, r_loc = synth.make_team_local_rewards(cfg, cfg.n_resp, levels=4)
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(gpu_device)
+    f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(gpu_device)
+    say(f"[group_advantage_mixed] large groups R={cfg.n_resp}")
+    out = api.at_grpo_group_advantage_mixed(i32(st.env_id), i32(st.agent_id), i32(st.turn_id), f32(r_team),
+                                            f32(r_loc), 0.5, cfg.E, cfg.N, cfg.T)
+    torch.cuda.synchronize()
+    mixed = orc.mix_rewards(r_team, r_loc, 0.5)
+    st.reward = mixed
+    check_group_advantage(out, st, cfg)
+    key = orc.group_key(st.env_id, st.agent_id, st.turn_id, cfg.N, cfg.T)
+    gid, G, _, _ = orc.group_segments(key)
+    assert np.array_equal(host(out["best"])[:G], orc.select_candidates(mixed, gid, G))
+    skipped = api.at_grpo_group_advantage_mixed(i32(st.env_id), i32(st.agent_id), i32(st.turn_id),
+                                                f32(r_team), f32(r_loc), 0.5, cfg.E, cfg.N, cfg.T,
+                                                want_best=False, want_stats=False)
+    torch.cuda.synchronize()
+    assert skipped["best"] is None and torch.equal(skipped["adv"], out["adv"])
 
 
 @pytest.mark.gpu
