@@ -22,6 +22,8 @@ Paper passages followed (arXiv 2510.11062):
                                                         Assignment", Eq. (3)
   * greedy choice of the executed candidate            -- Alg. 1 / Sec. 4.1 "Tree-structured
                                                         Sampling"
+  * update of policy m: gradient clipping, Adam        -- Alg. 1 Phase 2; App. C.1 (clip 1.0,
+                                                        lr 1e-6, weight decay 0.01)
 
 Readings taken where the paper is silent (all are parameters):
   * F_norm in Eq. (1) is the standard deviation; population (ddof=0) by default; the
@@ -360,3 +362,63 @@ def policy_loss_bwd(hidden, W_list, token_id, mask, cu_seqlens, resp_agent, head
     out = dict(fwd)
     out.update(d_hidden=d_hidden, dW=dW, g=g)
     return out
+
+
+# --------------------------------------------------------------------------------------
+# After the path: the update of the head (Alg. 1 Phase 2 "update policy m"; App. C.1)
+# --------------------------------------------------------------------------------------
+def global_grad_norm(grads) -> float:
+    """L2 norm over all the gradient arrays taken together (what "gradient clipping at 1.0"
+    of App. C.1 measures)."""
+    total = 0.0
+    for g in grads:
+        g = np.asarray(g, dtype=np.float64)
+        total += float((g * g).sum())
+    return float(np.sqrt(total))
+
+
+def clip_coefficient(norm: float, max_norm: float) -> float:
+    """Factor every gradient is multiplied by: max_norm / (norm + 1e-6), never above 1."""
+    return min(1.0, max_norm / (norm + 1e-6))
+
+
+def adam_step(w, g, m, v, step: int, lr: float = 1e-6, beta1: float = 0.9, beta2: float = 0.999,
+              eps: float = 1e-8, weight_decay: float = 0.01, decoupled: bool = True):
+    """One Adam step on fp64 arrays; returns (w, m, v) after the step.  step counts from 1.
+
+    m <- beta1 m + (1 - beta1) g,  v <- beta2 v + (1 - beta2) g^2,
+    w <- w - lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+    Weight decay (App. C.1 gives the value, not the form):
+      decoupled: w is first scaled by (1 - lr * weight_decay)            (default reading)
+      coupled:   g <- g + weight_decay * w before the moments (L2 penalty)
+    """
+    w = np.asarray(w, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    m = np.asarray(m, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    if decoupled:
+        w = w * (1.0 - lr * weight_decay)
+    else:
+        g = g + weight_decay * w
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** step)
+    v_hat = v / (1.0 - beta2 ** step)
+    w = w - lr * m_hat / (np.sqrt(v_hat) + eps)
+    return w, m, v
+
+
+def head_update(W_list, dW_list, m_list, v_list, step: int, max_grad_norm: float = 1.0, **adam):
+    """Clip the gradients of all heads by their joint norm, then one Adam step per head.
+
+    Returns dict(W=[...], m=[...], v=[...], grad_norm=float) in fp64 (the norm is the one before
+    clipping)."""
+    norm = global_grad_norm(dW_list)
+    c = clip_coefficient(norm, max_grad_norm) if max_grad_norm > 0 else 1.0
+    Ws, ms, vs = [], [], []
+    for w, g, m, v in zip(W_list, dW_list, m_list, v_list):
+        w2, m2, v2 = adam_step(w, np.asarray(g, dtype=np.float64) * c, m, v, step, **adam)
+        Ws.append(w2)
+        ms.append(m2)
+        vs.append(v2)
+    return dict(W=Ws, m=ms, v=vs, grad_norm=norm)

@@ -553,3 +553,80 @@ def test_selection_matches_brute_force_and_tie_rule():
     gid2 = np.array([0, 1, 1, 1, 2, 2])
     r2 = np.array([0.3, 0.5, 0.5, 0.5, 0.0, 1.0], dtype=np.float32)
     assert orc.select_candidates(r2, gid2, 3).tolist() == [0, 1, 5]
+
+
+# ----------------------------------------------------------------------------------------
+# the update of the head: gradient clipping and Adam (App. C.1)
+# ----------------------------------------------------------------------------------------
+def _rand_state(seed, shape=(7, 5)):
+    rng = np.random.default_rng(seed)
+    w = rng.standard_normal(shape) * 0.02
+    g = rng.standard_normal(shape) * 1e-3
+    return w, g
+
+
+@pytest.mark.parametrize("decoupled", [True, False])
+def test_adam_matches_the_library_optimiser_over_several_steps(decoupled):
+    w0, _ = _rand_state(1)
+    p = torch.nn.Parameter(torch.tensor(w0, dtype=torch.float64))
+    kw = dict(lr=1e-3, betas=(0.9, 0.999), eps=1e-8, weight_decay=0.01)
+    opt = torch.optim.AdamW([p], **kw) if decoupled else torch.optim.Adam([p], **kw)
+    w, m, v = w0.copy(), np.zeros_like(w0), np.zeros_like(w0)
+    for step in range(1, 6):
+        _, g = _rand_state(100 + step)
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        w, m, v = orc.adam_step(w, g, m, v, step, lr=1e-3, weight_decay=0.01, decoupled=decoupled)
+        assert np.allclose(w, p.detach().numpy(), rtol=1e-12, atol=1e-15), step
+    st = opt.state[p]
+    assert np.allclose(m, st["exp_avg"].numpy(), rtol=1e-12, atol=0)
+    assert np.allclose(v, st["exp_avg_sq"].numpy(), rtol=1e-12, atol=0)
+
+
+def test_adam_first_step_closed_form():
+    # from zero moments the bias-corrected moments are g and g^2: the step is lr * g / (|g| + eps)
+    w0, g = _rand_state(2)
+    lr, wd = 1e-6, 0.01
+    w1, m1, v1 = orc.adam_step(w0, g, np.zeros_like(w0), np.zeros_like(w0), 1, lr=lr, weight_decay=wd)
+    want = w0 * (1 - lr * wd) - lr * g / (np.abs(g) + 1e-8)
+    assert np.allclose(w1, want, rtol=1e-13, atol=0)
+    assert np.allclose(m1, 0.1 * g) and np.allclose(v1, 0.001 * g * g)
+    # zero gradient: only the decay acts, the moments stay zero
+    w2, m2, v2 = orc.adam_step(w0, np.zeros_like(w0), np.zeros_like(w0), np.zeros_like(w0), 1, lr=lr,
+                               weight_decay=wd)
+    assert np.allclose(w2, w0 * (1 - lr * wd), rtol=1e-15) and not m2.any() and not v2.any()
+
+
+def test_gradient_clipping_matches_the_library_routine():
+    rng = np.random.default_rng(4)
+    grads = [rng.standard_normal((6, 4)) * s for s in (0.8, 0.05)]
+    params = [torch.nn.Parameter(torch.zeros(6, 4, dtype=torch.float64)) for _ in grads]
+    for p, g in zip(params, grads):
+        p.grad = torch.tensor(g)
+    total = torch.nn.utils.clip_grad_norm_(params, max_norm=1.0)
+    norm = orc.global_grad_norm(grads)
+    assert math.isclose(norm, float(total), rel_tol=1e-12)
+    assert norm > 1.0
+    c = orc.clip_coefficient(norm, 1.0)
+    for p, g in zip(params, grads):
+        assert np.allclose(p.grad.numpy(), g * c, rtol=1e-12)
+    assert math.isclose(orc.global_grad_norm([g * c for g in grads]), 1.0, rel_tol=1e-5)
+    # a small gradient is left alone
+    assert orc.clip_coefficient(0.25, 1.0) == 1.0
+
+
+def test_head_update_clips_jointly_then_steps_each_head():
+    rng = np.random.default_rng(6)
+    Ws = [rng.standard_normal((5, 3)) * 0.02 for _ in range(2)]
+    gs = [rng.standard_normal((5, 3)) * 2.0 for _ in range(2)]
+    zeros = [np.zeros((5, 3)) for _ in range(2)]
+    out = orc.head_update(Ws, gs, zeros, zeros, step=1, max_grad_norm=1.0)
+    norm = math.sqrt(sum(float((g * g).sum()) for g in gs))
+    assert math.isclose(out["grad_norm"], norm, rel_tol=1e-14)
+    c = 1.0 / (norm + 1e-6)
+    for k in range(2):
+        w, m, v = orc.adam_step(Ws[k], gs[k] * c, zeros[k], zeros[k], 1)
+        assert np.array_equal(out["W"][k], w) and np.array_equal(out["m"][k], m) and np.array_equal(out["v"][k], v)
+    # clipping disabled
+    free = orc.head_update(Ws, gs, zeros, zeros, step=1, max_grad_norm=0.0)
+    assert np.allclose(free["m"][0], 0.1 * gs[0])
