@@ -73,7 +73,8 @@ typedef enum {
   AT_GRPO_CALL_TOKEN_LOGPROB = 1,
   AT_GRPO_CALL_POLICY_LOSS_FWD = 2,
   AT_GRPO_CALL_POLICY_LOSS_BWD = 3,
-  AT_GRPO_CALL_SURROGATE = 4
+  AT_GRPO_CALL_SURROGATE = 4,
+  AT_GRPO_CALL_HEAD_UPDATE = 5   /* size does not depend on the other arguments */
 } at_grpo_call;
 
 /*
@@ -196,6 +197,43 @@ int at_grpo_policy_loss_bwd(const at_grpo_batch* batch, const float* old_logp, c
                             float eps_low, float eps_high, int32_t agg, const float* grad_loss,
                             void* d_hidden, float* const* dW, int32_t accumulate_dW,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Hyper-parameters of the head update (App. C.1: Adam, learning rate 1e-6, weight decay 0.01,
+ * gradient clipping at 1.0; beta1, beta2 and eps are not stated there: 0.9, 0.999, 1e-8 are the
+ * customary values).
+ */
+typedef struct {
+  float lr, beta1, beta2, eps;
+  float weight_decay;
+  float max_grad_norm; /* 0 disables clipping                                                    */
+  int32_t step;        /* 1 for the first update (bias correction 1 - beta^step)                 */
+  int32_t decoupled;   /* 1: w <- w (1 - lr wd) before the step; 0: g <- g + wd w (L2 penalty)   */
+} at_grpo_adam;
+
+/*
+ * "Update policy m" of Alg. 1 (Phase 2) for the head weights, with App. C.1's recipe:
+ *   norm  = L2 norm of dW over all n_heads heads together
+ *   g     = dW * min(1, max_grad_norm / (norm + 1e-6))
+ *   m     <- beta1 m + (1 - beta1) g,   v <- beta2 v + (1 - beta2) g^2
+ *   w     <- w - lr wd w - (lr / (1 - beta1^step)) m / (sqrt(v / (1 - beta2^step)) + eps)
+ * (decoupled form; the coupled form adds wd w to g instead).  All arithmetic is fp32.
+ *   W        HOST array of n_heads device pointers, each [V, H] in `dtype`, updated in place
+ *   W_master HOST array of device pointers to the fp32 weights that are stepped, each [V, H];
+ *            required for AT_GRPO_BF16 (W then receives their bf16 rounding, nearest-even);
+ *            ignored for AT_GRPO_F32 (W itself is stepped)
+ *   dW       HOST array of device pointers, fp32 [V, H] (what at_grpo_policy_loss_bwd produced,
+ *            possibly accumulated over several mini-batches); read only
+ *   m, v     HOST arrays of device pointers, fp32 [V, H], Adam moments, updated in place
+ *   opt      host pointer
+ *   grad_norm[2]  device output: the norm before clipping, and the factor applied
+ * Every device pointer must be 16-byte aligned; H % 4 == 0.  Workspace: AT_GRPO_CALL_HEAD_UPDATE.
+ * The norm is reduced in a fixed order, so results are reproducible run to run.
+ */
+int at_grpo_head_update(int32_t dtype, int32_t H, int32_t V, int32_t n_heads, void* const* W,
+                        float* const* W_master, const float* const* dW, float* const* m,
+                        float* const* v, const at_grpo_adam* opt, float* grad_norm,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Bytes of workspace a call needs.  `batch` may be NULL for AT_GRPO_CALL_GROUP_ADVANTAGE; the

@@ -19,11 +19,13 @@ _lib = None
 
 AGG = {"token_mean": 0, "seq_mean_token_mean": 1}
 NORM = {"std": 0, "none": 1}
-CALL_GROUP_ADVANTAGE, CALL_TOKEN_LOGPROB, CALL_POLICY_LOSS_FWD, CALL_POLICY_LOSS_BWD, CALL_SURROGATE = range(5)
+CALL_GROUP_ADVANTAGE, CALL_TOKEN_LOGPROB, CALL_POLICY_LOSS_FWD, CALL_POLICY_LOSS_BWD, CALL_SURROGATE, \
+    CALL_HEAD_UPDATE = range(6)
+DTYPE = {torch.float32: 0, torch.bfloat16: 1}
 
 EXPORTS = [
     "at_grpo_group_advantage", "at_grpo_group_advantage_mixed", "at_grpo_token_logprob", "at_grpo_surrogate_from_logp",
-    "at_grpo_policy_loss_fwd", "at_grpo_policy_loss_bwd", "at_grpo_workspace_bytes",
+    "at_grpo_policy_loss_fwd", "at_grpo_policy_loss_bwd", "at_grpo_head_update", "at_grpo_workspace_bytes",
     "at_grpo_status_string", "at_grpo_version", "at_grpo_profile_enable", "at_grpo_profile_classes",
     "at_grpo_profile_read",
 ]
@@ -31,6 +33,12 @@ EXPORTS = [
 
 class AtGrpoError(RuntimeError):
     pass
+
+
+class _Adam(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("max_grad_norm", C.c_float), ("step", C.c_int32),
+                ("decoupled", C.c_int32)]
 
 
 class _Batch(C.Structure):
@@ -71,6 +79,10 @@ def load_library():
     lib.at_grpo_policy_loss_fwd.argtypes = [C.POINTER(_Batch), vp, vp, f32, f32, i32, vp, vp, vp, vp, vp,
                                             vp, sz, vp]
     lib.at_grpo_policy_loss_fwd.restype = C.c_int
+    lib.at_grpo_head_update.argtypes = [i32, i32, i32, i32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                        C.POINTER(_Adam), vp, vp, sz, vp]
+    lib.at_grpo_head_update.restype = C.c_int
     lib.at_grpo_policy_loss_bwd.argtypes = [C.POINTER(_Batch), vp, vp, vp, vp, f32, f32, i32, vp, vp,
                                             C.POINTER(C.c_void_p), i32, vp, sz, vp]
     lib.at_grpo_policy_loss_bwd.restype = C.c_int
@@ -255,6 +267,33 @@ def at_grpo_group_advantage_mixed(env_id, agent_id, turn_id, r_team, r_loc, alph
     _check(st, "at_grpo_group_advantage_mixed")
     out["workspace"] = ws
     return out
+
+
+def at_grpo_head_update(W, dW, m, v, step: int, W_master=None, lr: float = 1e-6, beta1: float = 0.9,
+                        beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.01,
+                        max_grad_norm: float = 1.0, decoupled: bool = True):
+    """Clip by the joint gradient norm, then one Adam step per head, in place on W / W_master / m / v.
+
+    W, dW, m, v (and W_master for bf16 heads) are lists of [V, H] tensors.  Returns
+    dict(grad_norm=tensor[2] (norm, factor), workspace)."""
+    lib = load_library()
+    n_heads = len(W)
+    _dev_check(*W, *dW, *m, *v, *(W_master or []))
+    V, H = W[0].shape
+    dtype = DTYPE[W[0].dtype]
+    dev = W[0].device
+
+    def arr(ts):
+        return (C.c_void_p * n_heads)(*[t.data_ptr() for t in ts])
+
+    masters = arr(W_master) if W_master is not None else None
+    opt = _Adam(lr, beta1, beta2, eps, weight_decay, max_grad_norm, step, 1 if decoupled else 0)
+    grad_norm = torch.zeros(2, dtype=torch.float32, device=dev)
+    ws = _workspace(lib.at_grpo_workspace_bytes(CALL_HEAD_UPDATE, None, 0, 0, 0, 0), dev)
+    st = lib.at_grpo_head_update(dtype, H, V, n_heads, arr(W), masters, arr(dW), arr(m), arr(v), C.byref(opt),
+                                 _ptr(grad_norm), _ptr(ws), ws.numel(), _stream())
+    _check(st, "at_grpo_head_update")
+    return dict(grad_norm=grad_norm, workspace=ws)
 
 
 def at_grpo_token_logprob(batch: Batch, want_lse: bool = True):

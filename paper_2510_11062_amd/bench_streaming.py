@@ -9,6 +9,8 @@ clip / masked reduction) and the backward coefficient at the C5 row count and on
 GB/s = algorithmic bytes / measured time, against the 8 TB/s HBM3E peak:
   grouping + advantages : 16 B read (3 ids + reward) + 12 B written (group id, perm, adv) per response
   surrogate stage       : 9 B read (logp, old_logp, mask) + 1 B written (clip mask) per row
+  head update           : 4 B read per parameter for the norm; 16 B read (gradient, two moments, fp32
+                          weight) + 14 B written (moments, fp32 weight, bf16 weight) for the step
 """
 from __future__ import annotations
 
@@ -85,6 +87,36 @@ def surrogate(dev, n_resp, mean_len, label):
             "frac": nbytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
+def head_update(dev, n_heads, V, H, label):
+    g = torch.Generator(device=dev)
+    g.manual_seed(7)
+    master = [torch.randn((V, H), generator=g, device=dev) * 0.02 for _ in range(n_heads)]
+    low = [w.to(torch.bfloat16) for w in master]
+    dW = [torch.randn((V, H), generator=g, device=dev) * 1e-4 for _ in range(n_heads)]
+    m = [torch.zeros_like(w) for w in master]
+    v = [torch.zeros_like(w) for w in master]
+    step = [0]
+
+    def fn():
+        step[0] += 1
+        api.at_grpo_head_update(low, dW, m, v, step[0], W_master=master)
+
+    dt = _time(fn)
+    api.at_grpo_profile_enable(True)
+    iters = 5
+    for _ in range(iters):
+        fn()
+    prof = api.at_grpo_profile_read()
+    api.at_grpo_profile_enable(False)
+    n = float(n_heads) * V * H
+    norm_ms, adam_ms = prof["grad_norm"][1] / iters, prof["adam"][1] / iters
+    return {"kernel": "head update (clip + Adam)", "workload": label, "parameters": int(n),
+            "us_per_call": dt * 1e6, "us_grad_norm": norm_ms * 1e3, "us_adam": adam_ms * 1e3,
+            "grad_norm_GBs": 4.0 * n / (norm_ms * 1e-3) / 1e9, "adam_GBs": 30.0 * n / (adam_ms * 1e-3) / 1e9,
+            "achieved": 34.0 * n / dt / 1e9, "unit": "GB/s", "peak": HBM_PEAK_GBS,
+            "frac": 34.0 * n / dt / 1e9 / HBM_PEAK_GBS}
+
+
 def main():
     if not torch.cuda.is_available():
         print("needs a GPU", file=sys.stderr)
@@ -100,6 +132,8 @@ def main():
                         shuffle=False))
     out.append(surrogate(dev, 6144, 290, "C5 row count (~1.8 M rows)"))
     out.append(surrogate(dev, 6144 * 16, 290, "16x twin of C5 (~28 M rows)"))
+    out.append(head_update(dev, 1, 151936, 2048, "C2 head: V=151936 H=2048, bf16 weights + fp32 master"))
+    out.append(head_update(dev, 2, 151936, 4096, "C3 heads: 2 x (V=151936 H=4096)"))
     for o in out:
         print(json.dumps(o))
 

@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libat_grpo.so")
-SOURCES = ["api.hip", "group_advantage.hip", "token_kernels.hip", "head_kernels.hip"]
+SOURCES = ["api.hip", "group_advantage.hip", "token_kernels.hip", "head_kernels.hip", "optimizer.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -9,6 +9,7 @@
 namespace atg {
 
 size_t group_advantage_workspace(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn);
+size_t head_update_workspace();
 
 // ---- timing aid --------------------------------------------------------------------------------
 namespace {
@@ -19,7 +20,7 @@ struct ProfState {
 ProfState g_prof;
 const char* const kProfNames[PROF_N] = {"group_advantage", "token_prep", "head_fwd", "lse_combine",
                                         "surrogate", "coef", "transpose", "head_dz", "head_dh",
-                                        "head_dw", "fill"};
+                                        "head_dw", "fill", "grad_norm", "adam"};
 }  // namespace
 
 void prof_begin(int cls, hipStream_t s) {
@@ -188,6 +189,7 @@ extern "C" size_t at_grpo_workspace_bytes(int32_t which_call, const at_grpo_batc
                                           int32_t n_env, int32_t n_agent, int32_t n_turn) {
   if (which_call == AT_GRPO_CALL_GROUP_ADVANTAGE)
     return group_advantage_workspace(n_resp, n_env, n_agent, n_turn);
+  if (which_call == AT_GRPO_CALL_HEAD_UPDATE) return head_update_workspace();
   if (which_call < AT_GRPO_CALL_TOKEN_LOGPROB || which_call > AT_GRPO_CALL_SURROGATE) return 0;
   const bool tensors = which_call != AT_GRPO_CALL_SURROGATE;
   if (check_layout(batch, tensors) != AT_GRPO_OK) return 0;

@@ -62,6 +62,8 @@ enum ProfClass {
   PROF_HEAD_DH,        // dHidden = dZ W
   PROF_HEAD_DW,        // dW = dZ^T hidden
   PROF_FILL,           // buffer clears
+  PROF_GRAD_NORM,      // global gradient norm of the head update
+  PROF_ADAM,           // fused clip + Adam step
   PROF_N
 };
 

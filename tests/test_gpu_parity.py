@@ -65,6 +65,16 @@ def test_workspace_query_and_argument_errors_on_host():
     assert st == 1
     b.H = 2048
     assert lib.at_grpo_token_logprob(b, None, None, None, 0, None) == 1
+    # head update: fixed-size workspace; null arrays, bf16 without fp32 weights and step 0 are rejected
+    assert lib.at_grpo_workspace_bytes(api.CALL_HEAD_UPDATE, None, 0, 0, 0, 0) > 0
+    opt = api._Adam(1e-6, 0.9, 0.999, 1e-8, 0.01, 1.0, 1, 1)
+    assert lib.at_grpo_head_update(1, 64, 64, 1, None, None, None, None, None, opt, None, None, 0, None) == 1
+    one = (api.C.c_void_p * 1)(256)
+    assert lib.at_grpo_head_update(1, 64, 64, 1, one, None, one, one, one, opt, 256, None, 0, None) == 1
+    opt.step = 0
+    assert lib.at_grpo_head_update(0, 64, 64, 1, one, None, one, one, one, opt, 256, None, 0, None) == 1
+    opt.step = 1
+    assert lib.at_grpo_head_update(0, 64, 64, 1, one, None, one, one, one, opt, 256, None, 0, None) == 3
 
 
 # ---------------------------------------------------------------------------- S1 + S2
