@@ -50,9 +50,16 @@ def grouping(dev, E, N, T, K, label, shuffle=True):
     reward = torch.rand(R, generator=g, device=dev)
     fn = lambda: api.at_grpo_group_advantage(env, agent, turn, reward, E, N, T, want_stats=False)
     dt = _time(fn)
+    api.at_grpo_profile_enable(True)
+    iters = 10
+    for _ in range(iters):
+        fn()
+    k_us = api.at_grpo_profile_read()["group_advantage"][1] / iters * 1e3
+    api.at_grpo_profile_enable(False)
     nbytes = 28.0 * R
     return {"kernel": "group_advantage (S1+S2, whole call)", "workload": label, "responses": R,
-            "groups": E * N * T, "us_per_call": dt * 1e6, "achieved": nbytes / dt / 1e9, "unit": "GB/s",
+            "groups": E * N * T, "us_per_call": dt * 1e6, "us_on_stream": k_us,
+            "achieved": nbytes / dt / 1e9, "unit": "GB/s",
             "peak": HBM_PEAK_GBS, "frac": nbytes / dt / 1e9 / HBM_PEAK_GBS}
 
 

@@ -8,6 +8,9 @@
 // exclusive scans (present keys -> dense ids, member counts -> CSR offsets) -> scatter by the
 // arrival rank the histogram's atomic returned (arbitrary order) -> per-group ordering of the
 // segment and the fp32 statistics.  The final ordering makes every output deterministic.
+// Three launch shapes, same device functions: everything in one workgroup (small batches: one
+// launch), five launches with a one-workgroup scan (key boxes up to 65536), seven launches with a
+// three-kernel scan (anything larger).
 #include "common.hpp"
 
 namespace atg {
@@ -203,143 +206,131 @@ __device__ __forceinline__ void group_stats_seq(const int32_t* perm_seg, int n,
   *std_out = sd;
 }
 
-// groups of at most kSmallGroup members: one thread per group
-__global__ __launch_bounds__(256) void k_ga_finish_small(const int32_t* __restrict__ n_groups,
-                                                         const int32_t* __restrict__ seg_offsets,
-                                                         const int32_t* __restrict__ arrival,
-                                                         const float* __restrict__ reward, GaStat st,
-                                                         int32_t* perm, float* __restrict__ adv,
-                                                         float* __restrict__ group_mean,
-                                                         float* __restrict__ group_std) {
-  const int G = *n_groups;
-  const int stride = gridDim.x * 256;
-  for (int g = blockIdx.x * 256 + threadIdx.x; g < G; g += stride) {
-    const int off = seg_offsets[g], n = seg_offsets[g + 1] - off;
-    if (n > kSmallGroup) continue;
-    if (n <= 8) {
-      // whole group in registers: ranks by counting, sums taken in ascending-index order
-      int id[8];
-      float x[8];
+// One group of at most kSmallGroup members, handled by one thread: order the segment, Eq. (1).
+__device__ __forceinline__ void finish_group_by_thread(int g, const int32_t* __restrict__ seg_offsets,
+                                                       const int32_t* __restrict__ arrival,
+                                                       const float* __restrict__ reward, const GaStat& st,
+                                                       int32_t* perm, float* __restrict__ adv,
+                                                       float* __restrict__ group_mean,
+                                                       float* __restrict__ group_std) {
+  const int off = seg_offsets[g], n = seg_offsets[g + 1] - off;
+  if (n > kSmallGroup) return;
+  if (n <= 8) {
+    // whole group in registers: ranks by counting, sums taken in ascending-index order
+    int id[8];
+    float x[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) id[j] = (j < n) ? arrival[off + j] : 0x7fffffff;
+    for (int j = 0; j < 8; ++j) id[j] = (j < n) ? arrival[off + j] : 0x7fffffff;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) x[j] = (j < n) ? reward[id[j]] : 0.f;
-      int rank[8];
+    for (int j = 0; j < 8; ++j) x[j] = (j < n) ? reward[id[j]] : 0.f;
+    int rank[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        int c = 0;
+    for (int j = 0; j < 8; ++j) {
+      int c = 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) c += (id[i] < id[j]);
-        rank[j] = c;
-      }
-      float xs[8];      // rewards in perm order
-#pragma unroll
-      for (int pos = 0; pos < 8; ++pos) {
-        float v = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v = (rank[j] == pos && j < n) ? x[j] : v;
-        xs[pos] = v;
-      }
-      float sum = 0.f;
-      bool same = true;
-#pragma unroll
-      for (int pos = 0; pos < 8; ++pos)
-        if (pos < n) {
-          sum += xs[pos];
-          same = same && (xs[pos] == xs[0]);
-        }
-      float mean = same ? xs[0] : sum / static_cast<float>(n), sd = 0.f, ss = 0.f;
-#pragma unroll
-      for (int pos = 0; pos < 8; ++pos)
-        if (pos < n) {
-          const float d = xs[pos] - mean;
-          ss += d * d;
-        }
-      const int denom = n - st.ddof;
-      if (!same) sd = denom > 0 ? sqrtf(ss / static_cast<float>(denom)) : 0.f;
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (j < n) {
-          perm[off + rank[j]] = id[j];
-          float a = 0.f;
-          if (!same) a = (st.norm == AT_GRPO_NORM_STD) ? (x[j] - mean) / (sd + st.eps_std) : (x[j] - mean);
-          adv[id[j]] = a;
-        }
-      if (group_mean) group_mean[g] = mean;
-      if (group_std) group_std[g] = sd;
-      continue;
+      for (int i = 0; i < 8; ++i) c += (id[i] < id[j]);
+      rank[j] = c;
     }
-    for (int j = 0; j < n; ++j) {
-      const int rj = arrival[off + j];
-      int rank = 0;
-      for (int i = 0; i < n; ++i) rank += (arrival[off + i] < rj);
-      perm[off + rank] = rj;
+    float xs[8];      // rewards in perm order
+#pragma unroll
+    for (int pos = 0; pos < 8; ++pos) {
+      float v = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v = (rank[j] == pos && j < n) ? x[j] : v;
+      xs[pos] = v;
     }
-    // perm[off .. off+n) was written by this thread only
-    float mu, sd;
-    group_stats_seq(perm + off, n, reward, st, adv, &mu, &sd);
-    if (group_mean) group_mean[g] = mu;
-    if (group_std) group_std[g] = sd;
-  }
-}
-
-// larger groups: one wavefront per group; ranks by counting, statistics by lane 0 in perm order
-__global__ __launch_bounds__(256) void k_ga_finish_large(const int32_t* __restrict__ n_groups,
-                                                         const int32_t* __restrict__ seg_offsets,
-                                                         const int32_t* __restrict__ arrival,
-                                                         const float* __restrict__ reward, GaStat st,
-                                                         int32_t* perm, float* __restrict__ adv,
-                                                         float* __restrict__ group_mean,
-                                                         float* __restrict__ group_std) {
-  const int G = *n_groups;
-  const int lane = threadIdx.x & 63;
-  const int wave = (blockIdx.x * 256 + threadIdx.x) >> 6;
-  const int n_waves = (gridDim.x * 256) >> 6;
-  for (int g = wave; g < G; g += n_waves) {
-    const int off = seg_offsets[g], n = seg_offsets[g + 1] - off;
-    if (n <= kSmallGroup) continue;
-    for (int j = lane; j < n; j += 64) {
-      const int rj = arrival[off + j];
-      int rank = 0;
-      for (int i = 0; i < n; ++i) rank += (arrival[off + i] < rj);
-      perm[off + rank] = rj;
-    }
-    __threadfence();   // the ranks below are read back by other lanes of this wavefront
-    // statistics: lane-strided partial sums combined in a fixed order
-    const float x0 = reward[perm[off]];
     float sum = 0.f;
-    int same = 1;
-    for (int j = lane; j < n; j += 64) {
-      const float x = reward[perm[off + j]];
-      sum += x;
-      same &= (x == x0);
-    }
-    sum = wave_sum(sum);
-    sum = __shfl(sum, 0, 64);
-    same = __builtin_amdgcn_ballot_w64(same == 0) == 0ull;
-    float mean = sum / static_cast<float>(n), sd = 0.f;
-    if (same) {
-      for (int j = lane; j < n; j += 64) adv[perm[off + j]] = 0.f;
-      mean = x0;
-    } else {
-      float ss = 0.f;
-      for (int j = lane; j < n; j += 64) {
-        const float d = reward[perm[off + j]] - mean;
+    bool same = true;
+#pragma unroll
+    for (int pos = 0; pos < 8; ++pos)
+      if (pos < n) {
+        sum += xs[pos];
+        same = same && (xs[pos] == xs[0]);
+      }
+    float mean = same ? xs[0] : sum / static_cast<float>(n), sd = 0.f, ss = 0.f;
+#pragma unroll
+    for (int pos = 0; pos < 8; ++pos)
+      if (pos < n) {
+        const float d = xs[pos] - mean;
         ss += d * d;
       }
-      ss = wave_sum(ss);
-      ss = __shfl(ss, 0, 64);
-      const int denom = n - st.ddof;
-      sd = denom > 0 ? sqrtf(ss / static_cast<float>(denom)) : 0.f;
-      for (int j = lane; j < n; j += 64) {
-        const int r = perm[off + j];
-        adv[r] = (st.norm == AT_GRPO_NORM_STD) ? (reward[r] - mean) / (sd + st.eps_std) : (reward[r] - mean);
+    const int denom = n - st.ddof;
+    if (!same) sd = denom > 0 ? sqrtf(ss / static_cast<float>(denom)) : 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (j < n) {
+        perm[off + rank[j]] = id[j];
+        float a = 0.f;
+        if (!same) a = (st.norm == AT_GRPO_NORM_STD) ? (x[j] - mean) / (sd + st.eps_std) : (x[j] - mean);
+        adv[id[j]] = a;
       }
+    if (group_mean) group_mean[g] = mean;
+    if (group_std) group_std[g] = sd;
+    return;
+  }
+  for (int j = 0; j < n; ++j) {
+    const int rj = arrival[off + j];
+    int rank = 0;
+    for (int i = 0; i < n; ++i) rank += (arrival[off + i] < rj);
+    perm[off + rank] = rj;
+  }
+  // perm[off .. off+n) was written by this thread only
+  float mu, sd;
+  group_stats_seq(perm + off, n, reward, st, adv, &mu, &sd);
+  if (group_mean) group_mean[g] = mu;
+  if (group_std) group_std[g] = sd;
+}
+
+// One larger group, handled by one wavefront: ranks by counting, statistics combined in a fixed order.
+__device__ __forceinline__ void finish_group_by_wave(int g, int lane, const int32_t* __restrict__ seg_offsets,
+                                                     const int32_t* __restrict__ arrival,
+                                                     const float* __restrict__ reward, const GaStat& st,
+                                                     int32_t* perm, float* __restrict__ adv,
+                                                     float* __restrict__ group_mean,
+                                                     float* __restrict__ group_std) {
+  const int off = seg_offsets[g], n = seg_offsets[g + 1] - off;
+  if (n <= kSmallGroup) return;
+  for (int j = lane; j < n; j += 64) {
+    const int rj = arrival[off + j];
+    int rank = 0;
+    for (int i = 0; i < n; ++i) rank += (arrival[off + i] < rj);
+    perm[off + rank] = rj;
+  }
+  __threadfence();   // the ranks below are read back by other lanes of this wavefront
+  // statistics: lane-strided partial sums combined in a fixed order
+  const float x0 = reward[perm[off]];
+  float sum = 0.f;
+  int same = 1;
+  for (int j = lane; j < n; j += 64) {
+    const float x = reward[perm[off + j]];
+    sum += x;
+    same &= (x == x0);
+  }
+  sum = wave_sum(sum);
+  sum = __shfl(sum, 0, 64);
+  same = __builtin_amdgcn_ballot_w64(same == 0) == 0ull;
+  float mean = sum / static_cast<float>(n), sd = 0.f;
+  if (same) {
+    for (int j = lane; j < n; j += 64) adv[perm[off + j]] = 0.f;
+    mean = x0;
+  } else {
+    float ss = 0.f;
+    for (int j = lane; j < n; j += 64) {
+      const float d = reward[perm[off + j]] - mean;
+      ss += d * d;
     }
-    if (lane == 0) {
-      if (group_mean) group_mean[g] = mean;
-      if (group_std) group_std[g] = sd;
+    ss = wave_sum(ss);
+    ss = __shfl(ss, 0, 64);
+    const int denom = n - st.ddof;
+    sd = denom > 0 ? sqrtf(ss / static_cast<float>(denom)) : 0.f;
+    for (int j = lane; j < n; j += 64) {
+      const int r = perm[off + j];
+      adv[r] = (st.norm == AT_GRPO_NORM_STD) ? (reward[r] - mean) / (sd + st.eps_std) : (reward[r] - mean);
     }
+  }
+  if (lane == 0) {
+    if (group_mean) group_mean[g] = mean;
+    if (group_std) group_std[g] = sd;
   }
 }
 
@@ -382,9 +373,213 @@ __global__ __launch_bounds__(256) void k_ga_select(const int32_t* __restrict__ n
   }
 }
 
-__global__ void k_ga_clear(int32_t* __restrict__ p, int64_t n) {
+// ------------------------------------------------------------------------------------------------
+// The whole call in one workgroup, for the sizes a training step actually has (a few thousand
+// groups, a few ten thousand responses): histogram, scans and the key tables live in LDS and the
+// phases are separated by workgroup barriers instead of kernel boundaries, so the call costs one
+// launch instead of nine.  Same arithmetic and the same device functions as the multi-launch path.
+// ------------------------------------------------------------------------------------------------
+constexpr int kSingleThreads = 1024;
+constexpr int kSingleMaxKeys = 8192;     // 3 tables of this many ints in LDS (96 KiB)
+constexpr int kSingleMaxResp = 4096;     // beyond this the multi-launch path is faster
+
+struct GaMix {
+  const float* r_team;
+  const float* r_loc;
+  float alpha;
+  float* reward_out;
+};
+
+// exclusive scan of one int per thread over the 1024-thread workgroup; *total = sum
+__device__ __forceinline__ int block_exclusive_scan_1024(int v, int* lds16, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int up = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += up;
+  }
+  __syncthreads();
+  if (lane == 63) lds16[wave] = incl;
+  __syncthreads();
+  int base = 0, sum = 0;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) {
+    const int t = lds16[w];
+    if (w < wave) base += t;
+    sum += t;
+  }
+  *total = sum;
+  return base + incl - v;
+}
+
+__global__ __launch_bounds__(kSingleThreads) void k_ga_single(
+    GaArgs a, GaMix mix, GaStat st, int n_keys, int32_t* __restrict__ err, int32_t* __restrict__ key_of_resp,
+    int32_t* __restrict__ rank_of_resp, int32_t* __restrict__ arrival, int32_t* __restrict__ group_id,
+    int32_t* __restrict__ n_groups, int32_t* __restrict__ seg_offsets, int32_t* perm,
+    float* __restrict__ adv, float* __restrict__ group_mean, float* __restrict__ group_std,
+    int32_t* __restrict__ best) {
+  __shared__ int hist[kSingleMaxKeys];
+  __shared__ int gid_of_key[kSingleMaxKeys];
+  __shared__ int off_of_key[kSingleMaxKeys];
+  __shared__ int lds16[16];
+  __shared__ int s_groups;
+  const int tid = threadIdx.x;
+  if (tid == 0) *err = 0;
+  for (int k = tid; k < n_keys; k += kSingleThreads) hist[k] = 0;
+  if (mix.r_team) {
+#pragma clang fp contract(off)
+    for (int r = tid; r < a.n_resp; r += kSingleThreads) {
+      const float prod = mix.alpha * mix.r_team[r];
+      mix.reward_out[r] = prod + mix.r_loc[r];      // read back below by the thread that wrote it
+    }
+  }
+  __syncthreads();
+
+  // histogram: the atomic's return value is the arrival rank inside the group
+  for (int r = tid; r < a.n_resp; r += kSingleThreads) {
+    bool ok;
+    const int64_t k64 = key_of(a, r, &ok);
+    int key = -1;
+    if (ok) {
+      key = static_cast<int>(k64);
+      const float x = a.reward[r];
+      if (!(fabsf(x) <= 3.402823466e38f)) atomicOr(err, AT_GRPO_DATA_REWARD);
+      rank_of_resp[r] = atomicAdd(&hist[key], 1);
+    } else {
+      atomicOr(err, AT_GRPO_DATA_ID_RANGE);
+    }
+    key_of_resp[r] = key;
+  }
+  __syncthreads();
+
+  // scans over the key box: present keys -> dense ids, member counts -> CSR offsets
+  const int per = (n_keys + kSingleThreads - 1) / kSingleThreads;     // <= 8
+  const int k0 = tid * per;
+  int p = 0, c = 0;
+  for (int e = 0; e < per; ++e) {
+    const int h = (k0 + e < n_keys) ? hist[k0 + e] : 0;
+    p += (h > 0);
+    c += h;
+  }
+  int tot_p, tot_c;
+  int gp = block_exclusive_scan_1024(p, lds16, &tot_p);
+  int gc = block_exclusive_scan_1024(c, lds16, &tot_c);
+  for (int e = 0; e < per; ++e) {
+    const int h = (k0 + e < n_keys) ? hist[k0 + e] : 0;
+    if (h > 0) {
+      gid_of_key[k0 + e] = gp;
+      off_of_key[k0 + e] = gc;
+      seg_offsets[gp] = gc;
+      ++gp;
+      gc += h;
+    }
+  }
+  if (tid == 0) {
+    *n_groups = tot_p;
+    seg_offsets[tot_p] = tot_c;
+    s_groups = tot_p;
+  }
+  __syncthreads();
+
+  // scatter by arrival rank
+  for (int r = tid; r < a.n_resp; r += kSingleThreads) {
+    const int key = key_of_resp[r];
+    if (key < 0) {
+      group_id[r] = -1;
+      adv[r] = 0.f;
+      continue;
+    }
+    group_id[r] = gid_of_key[key];
+    arrival[off_of_key[key] + rank_of_resp[r]] = r;
+  }
+  __syncthreads();   // arrival and seg_offsets (global) are read by other threads below
+
+  const int G = s_groups;
+  for (int g = tid; g < G; g += kSingleThreads)
+    finish_group_by_thread(g, seg_offsets, arrival, a.reward, st, perm, adv, group_mean, group_std);
+  const int lane = tid & 63, wave = tid >> 6;
+  for (int g = wave; g < G; g += kSingleThreads / 64)
+    finish_group_by_wave(g, lane, seg_offsets, arrival, a.reward, st, perm, adv, group_mean, group_std);
+  if (best) {
+    __syncthreads();   // perm is complete
+    for (int g = tid; g < G; g += kSingleThreads) {
+      const int off = seg_offsets[g], n = seg_offsets[g + 1] - off;
+      int top = perm[off];
+      float xt = a.reward[top];
+      for (int j = 1; j < n; ++j) {
+        const int r = perm[off + j];
+        const float x = a.reward[r];
+        if (x > xt) {
+          xt = x;
+          top = r;
+        }
+      }
+      best[g] = top;
+    }
+  }
+}
+
+// both finishing roles in one launch: the first n_small blocks take the small groups (a thread each),
+// the remaining blocks the larger ones (a wavefront each)
+__global__ __launch_bounds__(256) void k_ga_finish(int n_small, const int32_t* __restrict__ n_groups,
+                                                   const int32_t* __restrict__ seg_offsets,
+                                                   const int32_t* __restrict__ arrival,
+                                                   const float* __restrict__ reward, GaStat st, int32_t* perm,
+                                                   float* __restrict__ adv, float* __restrict__ group_mean,
+                                                   float* __restrict__ group_std) {
+  const int G = *n_groups;
+  if (static_cast<int>(blockIdx.x) < n_small) {
+    const int stride = n_small * 256;
+    for (int g = blockIdx.x * 256 + threadIdx.x; g < G; g += stride)
+      finish_group_by_thread(g, seg_offsets, arrival, reward, st, perm, adv, group_mean, group_std);
+  } else {
+    const int lane = threadIdx.x & 63;
+    const int wave = ((blockIdx.x - n_small) * 256 + threadIdx.x) >> 6;
+    const int n_waves = ((gridDim.x - n_small) * 256) >> 6;
+    for (int g = wave; g < G; g += n_waves)
+      finish_group_by_wave(g, lane, seg_offsets, arrival, reward, st, perm, adv, group_mean, group_std);
+  }
+}
+
+// both scans over a key box of at most kScanSingleKeys keys in one workgroup
+constexpr int kScanSingleKeys = 65536;
+__global__ __launch_bounds__(kSingleThreads) void k_ga_scan_single(const int32_t* __restrict__ hist, int n_keys,
+                                                                   int32_t* __restrict__ gid_of_key,
+                                                                   int32_t* __restrict__ n_groups,
+                                                                   int32_t* __restrict__ seg_offsets) {
+  __shared__ int lds16[16];
+  const int per = (n_keys + kSingleThreads - 1) / kSingleThreads;
+  const int k0 = threadIdx.x * per;
+  int p = 0, c = 0;
+  for (int e = 0; e < per; ++e) {
+    const int h = (k0 + e < n_keys) ? hist[k0 + e] : 0;
+    p += (h > 0);
+    c += h;
+  }
+  int tot_p, tot_c;
+  int gp = block_exclusive_scan_1024(p, lds16, &tot_p);
+  int gc = block_exclusive_scan_1024(c, lds16, &tot_c);
+  for (int e = 0; e < per; ++e) {
+    const int h = (k0 + e < n_keys) ? hist[k0 + e] : 0;
+    if (h > 0) {
+      gid_of_key[k0 + e] = gp;
+      seg_offsets[gp] = gc;
+      ++gp;
+      gc += h;
+    }
+  }
+  if (threadIdx.x == 0) {
+    *n_groups = tot_p;
+    seg_offsets[tot_p] = tot_c;
+  }
+}
+
+// clears two ranges in one launch
+__global__ void k_ga_clear2(int32_t* __restrict__ p, int64_t n, int32_t* __restrict__ q, int64_t nq) {
   const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
   for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < nq; i += stride) q[i] = 0;
 }
 
 struct GaPlan {
@@ -445,6 +640,16 @@ int run_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   ProfScope ps(PROF_GROUP, s);
 
+  if (p.n_keys <= kSingleMaxKeys && n_resp <= kSingleMaxResp) {
+    const GaMix mix{r_team, r_loc, alpha, reward_out};
+    const GaArgs a1{n_resp, n_env, n_agent, n_turn, env_id, agent_id, turn_id, r_team ? reward_out : reward};
+    const GaStat st1{eps_std, ddof, norm};
+    hipLaunchKernelGGL(k_ga_single, dim3(1), dim3(kSingleThreads), 0, s, a1, mix, st1, static_cast<int>(p.n_keys),
+                       p.err, p.key_of_resp, p.rank_of_resp, p.arrival, group_id, n_groups, seg_offsets, perm, adv,
+                       group_mean, group_std, best);
+    ATG_LAUNCH_CHECK();
+    return AT_GRPO_OK;
+  }
   if (r_team) {
     // the mixed reward is an output; everything below reads it
     hipLaunchKernelGGL(k_ga_mix, dim3(static_cast<unsigned>(ceil_div(n_resp, 256))), dim3(256), 0, s, n_resp,
@@ -457,34 +662,34 @@ int run_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t 
   const unsigned rb = static_cast<unsigned>(ceil_div(n_resp, 256));
   const unsigned kb = static_cast<unsigned>(p.n_blocks);
 
-  // err word and histogram are contiguous in the plan only by accident; clear them separately
-  hipLaunchKernelGGL(k_ga_clear, dim3(1), dim3(64), 0, s, p.err, int64_t{64});
-  ATG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_ga_clear, dim3(static_cast<unsigned>(ceil_div(p.n_keys, 1024) > 4096 ? 4096 : ceil_div(p.n_keys, 1024))),
-                     dim3(256), 0, s, p.hist, p.n_keys);
+  hipLaunchKernelGGL(k_ga_clear2, dim3(static_cast<unsigned>(ceil_div(p.n_keys, 1024) > 4096 ? 4096 : ceil_div(p.n_keys, 1024))),
+                     dim3(256), 0, s, p.hist, p.n_keys, p.err, int64_t{64});
   ATG_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_ga_hist, dim3(rb), dim3(256), 0, s, a, p.err, p.hist, p.key_of_resp, p.rank_of_resp);
   ATG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_ga_scan_partial, dim3(kb), dim3(256), 0, s, p.hist, p.n_keys, p.bsum_p, p.bsum_c);
-  ATG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_ga_scan_top, dim3(1), dim3(256), 0, s, p.n_blocks, p.bsum_p, p.bsum_c, n_groups,
-                     seg_offsets);
-  ATG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_ga_scan_apply, dim3(kb), dim3(256), 0, s, p.hist, p.n_keys, p.bsum_p, p.bsum_c,
-                     p.gid_of_key, seg_offsets);
-  ATG_LAUNCH_CHECK();
+  if (p.n_keys <= kScanSingleKeys) {
+    hipLaunchKernelGGL(k_ga_scan_single, dim3(1), dim3(kSingleThreads), 0, s, p.hist, static_cast<int>(p.n_keys),
+                       p.gid_of_key, n_groups, seg_offsets);
+    ATG_LAUNCH_CHECK();
+  } else {
+    hipLaunchKernelGGL(k_ga_scan_partial, dim3(kb), dim3(256), 0, s, p.hist, p.n_keys, p.bsum_p, p.bsum_c);
+    ATG_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_ga_scan_top, dim3(1), dim3(256), 0, s, p.n_blocks, p.bsum_p, p.bsum_c, n_groups,
+                       seg_offsets);
+    ATG_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_ga_scan_apply, dim3(kb), dim3(256), 0, s, p.hist, p.n_keys, p.bsum_p, p.bsum_c,
+                       p.gid_of_key, seg_offsets);
+    ATG_LAUNCH_CHECK();
+  }
   hipLaunchKernelGGL(k_ga_scatter, dim3(rb), dim3(256), 0, s, n_resp, p.key_of_resp, p.rank_of_resp,
                      p.gid_of_key, seg_offsets, group_id, p.arrival, adv);
   ATG_LAUNCH_CHECK();
-  // at most min(R, keys) groups exist; both finishing kernels stride over them
+  // at most min(R, keys) groups exist; both finishing roles stride over them
   const int64_t g_max = n_resp < p.n_keys ? n_resp : p.n_keys;
   const unsigned fs = static_cast<unsigned>(ceil_div(g_max, 256) > 4096 ? 4096 : ceil_div(g_max, 256));
   const unsigned fl = static_cast<unsigned>(ceil_div(g_max, 4) > 4096 ? 4096 : ceil_div(g_max, 4));
-  hipLaunchKernelGGL(k_ga_finish_small, dim3(fs), dim3(256), 0, s, n_groups, seg_offsets, p.arrival, reward,
-                     st, perm, adv, group_mean, group_std);
-  ATG_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_ga_finish_large, dim3(fl), dim3(256), 0, s, n_groups, seg_offsets, p.arrival, reward,
-                     st, perm, adv, group_mean, group_std);
+  hipLaunchKernelGGL(k_ga_finish, dim3(fs + fl), dim3(256), 0, s, static_cast<int>(fs), n_groups, seg_offsets,
+                     p.arrival, reward, st, perm, adv, group_mean, group_std);
   ATG_LAUNCH_CHECK();
   if (best) {
     hipLaunchKernelGGL(k_ga_select, dim3(fs), dim3(256), 0, s, n_groups, seg_offsets, perm, reward, best);

@@ -112,7 +112,8 @@ def test_group_advantage_matches_oracle_full_size(gpu_device, name):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("variant", ["early_termination", "singletons", "large_groups", "ddof1", "norm_none"])
+@pytest.mark.parametrize("variant", ["early_termination", "singletons", "large_groups", "ddof1", "norm_none",
+                                     "many_keys", "many_keys_early_termination"])
 def test_group_advantage_variants(gpu_device, variant):
     base = synth.CONFIGS["C4"]
     kw = {}
@@ -122,6 +123,11 @@ def test_group_advantage_variants(gpu_device, variant):
         cfg = replace(base, E=50, K=1)
     elif variant == "large_groups":
         cfg = replace(base, E=3, N=1, T=2, K=700, reward_kind="uniform", forced_equal_groups=1)
+    elif variant == "many_keys":
+        # more keys and responses than the one-workgroup path takes: the multi-launch pipeline
+        cfg = replace(base, E=2100, N=2, T=2, K=8, reward_kind="mixed")
+    elif variant == "many_keys_early_termination":
+        cfg = replace(base, E=1200, N=2, T=4, K=3, drop_tail_frac=0.3)
     elif variant == "ddof1":
         cfg = replace(base, E=30)
         kw = dict(ddof=1)
@@ -131,6 +137,32 @@ def test_group_advantage_variants(gpu_device, variant):
     say(f"[group_advantage] variant {variant} R={cfg.n_resp}")
     st = synth.make_structure(cfg)
     check_group_advantage(run_group_advantage(gpu_device, st, cfg, **kw), st, cfg, **kw)
+
+
+@pytest.mark.gpu
+def test_group_advantage_key_box_beyond_one_scan_block(gpu_device):
+    """80000 keys, 240000 responses: the three-kernel scan.  Integers are compared in full; the
+    advantages on a sample of groups the oracle handles one by one."""
+    cfg = replace(synth.CONFIGS["C4"], E=40000, N=2, T=1, K=3, reward_kind="uniform", forced_equal_groups=50)
+    st = synth.make_structure(cfg)
+    say(f"[group_advantage] large key box R={cfg.n_resp} keys={cfg.E * cfg.N * cfg.T}")
+    out = run_group_advantage(gpu_device, st, cfg)
+    key = orc.group_key(st.env_id, st.agent_id, st.turn_id, cfg.N, cfg.T)
+    gid, G, offs, perm = orc.group_segments(key)
+    assert int(out["n_groups"].item()) == G
+    assert np.array_equal(host(out["group_id"]), gid)
+    assert np.array_equal(host(out["seg_offsets"])[:G + 1], offs)
+    assert np.array_equal(host(out["perm"]), perm)
+    pick = np.random.default_rng(1).choice(G, size=400, replace=False)
+    pick.sort()
+    members = np.concatenate([perm[offs[g]:offs[g + 1]] for g in pick])
+    sub_gid = np.repeat(np.arange(400), [offs[g + 1] - offs[g] for g in pick])
+    adv, mean, std = orc.group_advantage(st.reward[members], sub_gid, 400)
+    got = host(out["adv"]).astype(np.float64)[members]
+    assert np.all(got[std[sub_gid] == 0] == 0)
+    assert np.allclose(got, adv, rtol=1e-4, atol=1e-6)
+    assert np.allclose(host(out["group_mean"])[pick], mean, rtol=1e-4, atol=1e-7)
+    assert np.allclose(host(out["group_std"])[pick], std, rtol=1e-4, atol=1e-7)
 
 
 @pytest.mark.gpu
