@@ -8,7 +8,8 @@ latency-bound: at most 20480 responses) and on a scaled-up twin with the same gr
 clip / masked reduction) and the backward coefficient at the C5 row count and on a 16x twin.
 GB/s = algorithmic bytes / measured time, against the 8 TB/s HBM3E peak:
   grouping + advantages : 16 B read (3 ids + reward) + 12 B written (group id, perm, adv) per response
-  surrogate stage       : 9 B read (logp, old_logp, mask) + 1 B written (clip mask) per row
+  surrogate stage       : 13 B read (logp, old_logp, token id for the range check, mask) + 1 B written
+                          (clip mask) per row
   head update           : 4 B read per parameter for the norm; 16 B read (gradient, two moments, fp32
                           weight) + 14 B written (moments, fp32 weight, bf16 weight) for the step
 """
@@ -84,7 +85,7 @@ def surrogate(dev, n_resp, mean_len, label):
         fn()
     prof = api.at_grpo_profile_read()
     api.at_grpo_profile_enable(False)
-    nbytes = 10.0 * n_tok
+    nbytes = 14.0 * n_tok      # logp 4 + old_logp 4 + token id 4 (range check) + mask 1 read, clip mask 1 written
     k_ms = prof["surrogate"][1] / iters
     p_ms = prof["token_prep"][1] / iters
     return {"kernel": "surrogate stage (S5+S6)", "workload": label, "rows": n_tok,

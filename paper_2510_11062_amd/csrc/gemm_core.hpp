@@ -121,9 +121,10 @@ constexpr int kLdSub3 = kLdPerStep * 3 / 8;       // requested in sub-step 3 of 
 constexpr int kLdSub0 = kLdPerStep * 3 / 8;       // ... in sub-step 0 of the step before
 constexpr int kLdSub1 = kLdPerStep - kLdSub3 - kLdSub0;
 
-// index of the MFMA after which load k of `cnt` is issued within one sub-step
+// index of the MFMA after which load k of `cnt` is issued within one sub-step: evenly spread, so
+// that the eight wavefronts of the workgroup do not queue up behind each other at the load unit
 __device__ __forceinline__ constexpr int load_slot(int k, int cnt) {
-  return (kMmPerSub - kRdPerSub >= cnt) ? kMmPerSub - cnt + k : ((k + 1) * kMmPerSub) / cnt - 1;
+  return ((2 * k + 1) * kMmPerSub) / (2 * cnt);
 }
 
 #define ATG_PIN() __builtin_amdgcn_sched_barrier(0)
