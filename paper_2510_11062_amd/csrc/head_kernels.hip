@@ -10,6 +10,8 @@
 // give dHidden = dZ W (k = vocab, both operands contiguous along k) and dW = dZ^T hidden
 // (k = tokens, both operands read k-major through transposing LDS reads).  The fp32 path keeps a
 // second, transposed copy of dZ instead.
+#include <type_traits>
+
 #include "gemm_core.hpp"
 #include "head_kernels.hpp"
 
@@ -305,40 +307,55 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
         nk, smem);
 
     const int vwave = tc.wm * (kTile / kWavesA);     // first vocab row (inside the tile) of this wavefront
+    // Tiles that lie fully inside the vocabulary and the token list (all but the last row / column of
+    // tiles) need no per-element range checks; the target's one-hot term is rare (one element in V per
+    // token) and is patched in behind a branch that is almost never taken.
+    const bool interior = (v0 + kTile <= V) && (t0 + kTile <= n);
+    auto emit = [&](auto guard_c) {
+      constexpr bool kGuard = decltype(guard_c)::value;
 #pragma unroll
-    for (int j = 0; j < kJB; ++j) {
-      const float g = gcol[j];
-      const bool live = tcol[j] < n;
+      for (int j = 0; j < kJB; ++j) {
+        const float g = gcol[j];
+        const float nl2 = -l2col[j];
+        const bool live = tcol[j] < n;
 #pragma unroll
-      for (int i = 0; i < kIB; ++i) {
+        for (int i = 0; i < kIB; ++i) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int vl = vwave + i * 32 + 8 * q + 4 * tc.half;   // first of 4 consecutive vocab rows
-          const int v = v0 + vl;
-          float d[4];
+          for (int q = 0; q < 4; ++q) {
+            const int vl = vwave + i * 32 + 8 * q + 4 * tc.half;   // first of 4 consecutive vocab rows
+            const int v = v0 + vl;
+            float d[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float p = fast_exp2(fmaf(acc[i][j][q * 4 + e], kLog2e, -l2col[j]));
-            float x = -g * p;
-            if (v + e == ycol[j]) x += g;
-            d[e] = (v + e < V && live) ? x : 0.f;   // k padding and rows past the count are 0
-          }
-          if (kStage) {
-            uint2 u;
-            u.x = pack_bf16x2(d[0], d[1]);
-            u.y = pack_bf16x2(d[2], d[3]);
-            *reinterpret_cast<uint2*>(smem + tc.b_row(j) * kDzRowStride + vl * 2) = u;
-          } else {
-            if (v < Vp) Pack4<T>::store(dZ + static_cast<size_t>(tcol[j]) * Vp + v, d[0], d[1], d[2], d[3]);
-          }
-          if (!kStage) {
+            for (int e = 0; e < 4; ++e) d[e] = -g * fast_exp2(fmaf(acc[i][j][q * 4 + e], kLog2e, nl2));
+            const int rel = ycol[j] - v;
+            if (static_cast<unsigned>(rel) < 4u) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (v + e < V) dZt[static_cast<size_t>(v + e) * TC + tcol[j]] = from_f32<T>(d[e]);
+              for (int e = 0; e < 4; ++e)
+                if (rel == e) d[e] += g;
+            }
+            if (kGuard) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) d[e] = (v + e < V && live) ? d[e] : 0.f;   // k padding, rows past the count
+            }
+            if (kStage) {
+              uint2 u;
+              u.x = pack_bf16x2(d[0], d[1]);
+              u.y = pack_bf16x2(d[2], d[3]);
+              *reinterpret_cast<uint2*>(smem + tc.b_row(j) * kDzRowStride + vl * 2) = u;
+            } else {
+              if (v < Vp) Pack4<T>::store(dZ + static_cast<size_t>(tcol[j]) * Vp + v, d[0], d[1], d[2], d[3]);
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (v + e < V) dZt[static_cast<size_t>(v + e) * TC + tcol[j]] = from_f32<T>(d[e]);
+            }
           }
         }
       }
-    }
+    };
+    if (interior)
+      emit(std::false_type{});
+    else
+      emit(std::true_type{});
     if (kStage) {
       __syncthreads();
       // dZ[t][v]: 32 threads x 16 bytes cover the 512 bytes of one token row of the staged tile
