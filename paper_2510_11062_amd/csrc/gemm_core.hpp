@@ -107,6 +107,15 @@ __device__ __forceinline__ uint32_t lds_address(const char* p) {
 // s_waitcnt vmcnt(0) only (expcnt and lgkmcnt left at their maxima)
 __device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
+// Workgroup barrier that orders LDS traffic only: waits for this wavefront's LDS operations
+// (lgkmcnt(0)), not for its outstanding global stores.  __syncthreads() would also wait until every
+// store issued so far has been acknowledged by memory, which an epilogue that has just written its
+// results does not need before the LDS buffer is reused.
+__device__ __forceinline__ void barrier_lds_only() {
+  __builtin_amdgcn_s_waitcnt(0xC07F);   // vmcnt and expcnt at their maxima, lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+}
+
 // Pinned k loop shared by both operand layouts.  Ops supplies
 //   mm(f, n)              MFMA group n (0..kIB*kJB-1) on fragment set f
 //   rd(stage, ks, f, n)   fetch of fragment n (0..kIB+kJB-1) of sub-step ks of `stage` into set f
@@ -192,14 +201,15 @@ __device__ __forceinline__ void pinned_k_loop(Ops& ops, int nk, char* smem) {
   // prologue: all of step 0 and the first loads of step 1, which may still be in flight afterwards
 #pragma unroll
   for (int d = 0; d < kLdPerStep; ++d) ops.ld(0, d);
+  // (a raw barrier: __syncthreads() would add a wait for every outstanding load and store)
   if (nk > 1) {
 #pragma unroll
     for (int d = 0; d < kLdSub3; ++d) ops.ld(1, d);
-    __builtin_amdgcn_s_waitcnt(0x0F70 | kLdSub3);   // vmcnt(kLdSub3)
+    __builtin_amdgcn_s_waitcnt(0x0070 | kLdSub3);   // vmcnt(kLdSub3) lgkmcnt(0)
   } else {
-    wait_direct_loads();
+    __builtin_amdgcn_s_waitcnt(0x0070);             // vmcnt(0) lgkmcnt(0)
   }
-  __syncthreads();
+  __builtin_amdgcn_s_barrier();
 #pragma unroll
   for (int n = 0; n < kRdPerSub; ++n) ops.rd(smem, 0, 0, n);
   int kt = 0;

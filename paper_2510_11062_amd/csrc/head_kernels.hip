@@ -134,7 +134,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
       }
     }
     // fold the four vocabulary quarters of the tile: one (max, sum) per token and vocabulary tile
-    __syncthreads();
+    barrier_lds_only();
     if (threadIdx.x < kTile && t0 + threadIdx.x < n) {
       float M = -INFINITY;
 #pragma unroll
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
       part_m[static_cast<size_t>(vt) * TC + t0 + threadIdx.x] = M;
       part_s[static_cast<size_t>(vt) * TC + t0 + threadIdx.x] = S;
     }
-    __syncthreads();
+    barrier_lds_only();   // the fold buffers are free again; the stores above need not have landed
   }
 }
 
@@ -373,7 +373,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
                                     (static_cast<size_t>(t0 + row) * Vp + v0 + col16 * 8) * 2) = u;
         }
       }
-      __syncthreads();
+      barrier_lds_only();   // every wavefront has read its part of the staged tile; its stores may still fly
     }
   }
 }
