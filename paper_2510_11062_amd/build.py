@@ -10,6 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libat_grpo.so")
+CLIENT = os.path.join(PKG, "abi_client")
 SOURCES = ["api.hip", "group_advantage.hip", "token_kernels.hip", "head_kernels.hip", "optimizer.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -28,6 +29,20 @@ def _compile(src: str) -> str:
     return obj
 
 
+def build_client(verbose: bool = True) -> str:
+    """A plain C99 caller of the library (gcc, the HIP C API): proof that the header is C and that the
+    struct layout a C compiler produces is the one the library reads."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = [os.environ.get("CC", "gcc"), "-std=c99", "-O1", "-Wall", "-Werror", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(rocm, "include"), "-I", os.path.join(ROOT, "include"),
+           os.path.join(CSRC, "abi_client.c"), "-o", CLIENT, "-L", PKG, "-lat_grpo",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    subprocess.run(cmd, check=True)
+    if verbose:
+        print("built", CLIENT)
+    return CLIENT
+
+
 def build(verbose: bool = True) -> str:
     with ThreadPoolExecutor(max_workers=4) as pool:
         objs = list(pool.map(_compile, SOURCES))
@@ -35,6 +50,7 @@ def build(verbose: bool = True) -> str:
     subprocess.run(cmd, check=True)
     if verbose:
         print("built", LIB)
+    build_client(verbose)
     return LIB
 
 
