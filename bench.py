@@ -75,9 +75,20 @@ def cpu_baseline(cfg, st, batch, old_logp, n_sample):
     t0 = time.perf_counter()
     orc.policy_loss_bwd(hidden, W, y, None, cu, None, None, old, adv, cfg.eps_clip, cfg.eps_clip)
     dt = time.perf_counter() - t0
+    cpu = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                cpu = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    n_all = int(valid.sum().item())
     return {"value": n / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"{n} response tokens of {cfg.name} on one head, fp64 numpy forward+backward "
-                      f"(one-token responses), {dt:.1f} s"}
+                      f"(one-token responses), {dt:.1f} s",
+            "host_cpu": cpu, "host_logical_cpus": os.cpu_count(),
+            "extrapolated_full_workload_s": n_all / (n / dt)}
 
 
 def main():
