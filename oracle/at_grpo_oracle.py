@@ -294,6 +294,37 @@ def policy_loss_from_logp(logp, old_logp, adv, mask, head_of_tok, resp_of_tok, n
     return loss, clip_mask, n_valid, w, ratio, sel, adv_tok
 
 
+def surrogate_diagnostics(logp, old_logp, adv, mask, head_of_tok, resp_of_tok, n_heads: int,
+                          eps_low: float, eps_high: float):
+    """Training diagnostics of Eq. (2)'s pieces, per policy, over its participating tokens:
+
+      counts[m] = (n, n_low, n_high, n_zero_grad): tokens, tokens with ratio below 1 - eps_low,
+                  above 1 + eps_high, and on the clipped branch (no gradient)
+      kl[m]     = mean of ratio - 1 - d: the non-negative sample estimate of KL(pi_old || pi_theta)
+                  from tokens drawn under pi_old (d = log ratio)
+      ratio[m]  = mean importance ratio
+    The paper reports none of these (its entropy coefficient is 0 and Eq. 2 has no KL term); they
+    are the usual monitors of a clipped-ratio update.  d is the fp32 difference the clip flags use.
+    """
+    w, n_valid = token_weights(mask, head_of_tok, resp_of_tok, n_heads, "token_mean")
+    adv64 = np.asarray(adv, dtype=np.float32).astype(np.float64)
+    adv_tok = np.where(resp_of_tok >= 0, adv64[np.maximum(resp_of_tok, 0)], 0.0)
+    _, ratio, clip_mask, _ = surrogate_terms(logp, old_logp, adv_tok, eps_low, eps_high)
+    d = (np.asarray(logp, dtype=np.float64).astype(np.float32) - np.asarray(old_logp, dtype=np.float32)).astype(np.float64)
+    counts = np.zeros((n_heads, 4), dtype=np.int64)
+    kl = np.zeros(n_heads, dtype=np.float64)
+    mean_ratio = np.zeros(n_heads, dtype=np.float64)
+    for k in range(n_heads):
+        rows = (w > 0) & (head_of_tok == k)
+        n = int(rows.sum())
+        counts[k] = (n, int(((clip_mask[rows] & CLIP_LOW) != 0).sum()), int(((clip_mask[rows] & CLIP_HIGH) != 0).sum()),
+                     int(((clip_mask[rows] & CLIP_ZERO_GRAD) != 0).sum()))
+        if n > 0:
+            kl[k] = (ratio[rows] - 1.0 - d[rows]).sum() / n
+            mean_ratio[k] = ratio[rows].sum() / n
+    return counts, kl, mean_ratio
+
+
 def policy_loss_fwd(hidden, W_list, token_id, mask, cu_seqlens, resp_agent, head_of_agent,
                     old_logp, adv, eps_low: float, eps_high: float, agg: str = "token_mean"):
     """S3..S6.  Returns dict(loss, logp, lse, clip_mask, n_valid)."""

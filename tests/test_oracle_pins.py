@@ -630,3 +630,57 @@ def test_head_update_clips_jointly_then_steps_each_head():
     # clipping disabled
     free = orc.head_update(Ws, gs, zeros, zeros, step=1, max_grad_norm=0.0)
     assert np.allclose(free["m"][0], 0.1 * gs[0])
+
+
+# ----------------------------------------------------------------------------------------
+# diagnostics of the clipped-ratio update
+# ----------------------------------------------------------------------------------------
+def _diag_inputs(d_values, adv_values):
+    n = len(d_values)
+    old = np.full(n, -2.0, dtype=np.float32)
+    logp = (old + np.asarray(d_values, dtype=np.float32)).astype(np.float32)
+    d32 = (logp - old).astype(np.float64)                  # what the method sees
+    head = np.zeros(n, dtype=np.int64)
+    resp = np.arange(n, dtype=np.int64)
+    return logp, old, np.asarray(adv_values, dtype=np.float32), head, resp, d32
+
+
+def test_diagnostics_on_policy_and_constant_shift():
+    logp, old, adv, head, resp, _ = _diag_inputs(np.zeros(50), np.linspace(-1, 1, 50))
+    counts, kl, ratio = orc.surrogate_diagnostics(logp, old, adv, None, head, resp, 1, 0.2, 0.2)
+    assert counts.tolist() == [[50, 0, 0, 0]] and kl[0] == 0.0 and ratio[0] == 1.0
+    # every token shifted by the same c: KL estimate e^c - 1 - c, mean ratio e^c (c inside the clip range)
+    logp, old, adv, head, resp, d32 = _diag_inputs(np.full(40, 0.125), np.ones(40))
+    counts, kl, ratio = orc.surrogate_diagnostics(logp, old, adv, None, head, resp, 1, 0.2, 0.2)
+    c = d32[0]
+    assert counts.tolist() == [[40, 0, 0, 0]]
+    assert math.isclose(kl[0], math.exp(c) - 1 - c, rel_tol=1e-12)
+    assert math.isclose(ratio[0], math.exp(c), rel_tol=1e-12)
+
+
+def test_diagnostics_counts_follow_the_clip_truth_table_and_kl_is_nonnegative():
+    #            below, A>0   below, A<0   inside   above, A>0   above, A<0   above, A=0
+    d = np.array([-0.5,        -0.5,        0.05,    0.4,         0.4,         0.4])
+    A = np.array([1.0,         -1.0,        1.0,     1.0,         -1.0,        0.0])
+    logp, old, adv, head, resp, d32 = _diag_inputs(d, A)
+    counts, kl, ratio = orc.surrogate_diagnostics(logp, old, adv, None, head, resp, 1, 0.2, 0.2)
+    assert counts.tolist() == [[6, 2, 3, 2]]          # zero gradient: (below, A<0) and (above, A>0)
+    want_kl = sum(math.exp(x) - 1 - x for x in d32) / 6
+    assert math.isclose(kl[0], want_kl, rel_tol=1e-12) and kl[0] > 0
+    rng = np.random.default_rng(8)
+    dd = rng.normal(0, 0.3, 500)
+    logp, old, adv, head, resp, _ = _diag_inputs(dd, rng.normal(0, 1, 500))
+    mask = (rng.random(500) < 0.7).astype(np.uint8)
+    head2 = rng.integers(0, 3, 500)
+    counts, kl, ratio = orc.surrogate_diagnostics(logp, old, adv, mask, head2, resp, 3, 0.2, 0.28)
+    assert np.all(kl >= 0) and counts[:, 0].sum() == int(mask.sum())
+    # brute force over the tokens of each head
+    lo, hi = math.log1p(-0.2), math.log1p(0.28)
+    d32 = (logp - old).astype(np.float64)
+    for k in range(3):
+        rows = [t for t in range(500) if mask[t] and head2[t] == k]
+        assert counts[k, 1] == sum(d32[t] < np.float32(lo) for t in rows)
+        assert counts[k, 2] == sum(d32[t] > np.float32(hi) for t in rows)
+        assert counts[k, 3] == sum((d32[t] > np.float32(hi) and adv[t] > 0) or (d32[t] < np.float32(lo) and adv[t] < 0)
+                                   for t in rows)
+        assert math.isclose(ratio[k], sum(math.exp(d32[t]) for t in rows) / len(rows), rel_tol=1e-12)
