@@ -74,7 +74,8 @@ typedef enum {
   AT_GRPO_CALL_POLICY_LOSS_FWD = 2,
   AT_GRPO_CALL_POLICY_LOSS_BWD = 3,
   AT_GRPO_CALL_SURROGATE = 4,
-  AT_GRPO_CALL_HEAD_UPDATE = 5   /* size does not depend on the other arguments */
+  AT_GRPO_CALL_HEAD_UPDATE = 5,  /* size does not depend on the other arguments */
+  AT_GRPO_CALL_DIAGNOSTICS = 6
 } at_grpo_call;
 
 /*
@@ -170,6 +171,19 @@ int at_grpo_surrogate_from_logp(const at_grpo_batch* batch, const float* logp, c
                                 const float* adv, float eps_low, float eps_high, int32_t agg,
                                 float* loss, uint8_t* clip_mask, int32_t* n_valid,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Monitors of the clipped-ratio update of Eq. (2), per policy, over the same participating rows as
+ * at_grpo_surrogate_from_logp (the paper reports none of them; its entropy coefficient is 0 and Eq. 2
+ * carries no KL term):
+ *   counts[n_heads][4]  rows, rows with d < lo, rows with d > hi, rows on the clipped branch
+ *                       (AT_GRPO_CLIP_LOW / _HIGH / _ZERO_GRAD counted), d = logp - old_logp in fp32
+ *   stats[n_heads][2]   mean of exp(d) - 1 - d (sample estimate of KL(pi_old || pi_theta)), mean exp(d)
+ * Sums are taken in a fixed order.  Workspace: AT_GRPO_CALL_DIAGNOSTICS (needs batch->n_resp only).
+ */
+int at_grpo_surrogate_diagnostics(const at_grpo_batch* batch, const float* logp, const float* old_logp,
+                                  const float* adv, float eps_low, float eps_high, int32_t* counts,
+                                  float* stats, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Forward of the policy loss: at_grpo_token_logprob followed by at_grpo_surrogate_from_logp.

@@ -20,11 +20,12 @@ _lib = None
 AGG = {"token_mean": 0, "seq_mean_token_mean": 1}
 NORM = {"std": 0, "none": 1}
 CALL_GROUP_ADVANTAGE, CALL_TOKEN_LOGPROB, CALL_POLICY_LOSS_FWD, CALL_POLICY_LOSS_BWD, CALL_SURROGATE, \
-    CALL_HEAD_UPDATE = range(6)
+    CALL_HEAD_UPDATE, CALL_DIAGNOSTICS = range(7)
 DTYPE = {torch.float32: 0, torch.bfloat16: 1}
 
 EXPORTS = [
     "at_grpo_group_advantage", "at_grpo_group_advantage_mixed", "at_grpo_token_logprob", "at_grpo_surrogate_from_logp",
+    "at_grpo_surrogate_diagnostics",
     "at_grpo_policy_loss_fwd", "at_grpo_policy_loss_bwd", "at_grpo_head_update", "at_grpo_workspace_bytes",
     "at_grpo_status_string", "at_grpo_version", "at_grpo_profile_enable", "at_grpo_profile_classes",
     "at_grpo_profile_read",
@@ -76,6 +77,8 @@ def load_library():
     lib.at_grpo_surrogate_from_logp.argtypes = [C.POINTER(_Batch), vp, vp, vp, f32, f32, i32, vp, vp, vp,
                                                 vp, sz, vp]
     lib.at_grpo_surrogate_from_logp.restype = C.c_int
+    lib.at_grpo_surrogate_diagnostics.argtypes = [C.POINTER(_Batch), vp, vp, vp, f32, f32, vp, vp, vp, sz, vp]
+    lib.at_grpo_surrogate_diagnostics.restype = C.c_int
     lib.at_grpo_policy_loss_fwd.argtypes = [C.POINTER(_Batch), vp, vp, f32, f32, i32, vp, vp, vp, vp, vp,
                                             vp, sz, vp]
     lib.at_grpo_policy_loss_fwd.restype = C.c_int
@@ -323,6 +326,22 @@ def at_grpo_surrogate_from_logp(batch: Batch, logp, old_logp, adv, eps_low: floa
                                          ws.numel(), _stream())
     _check(st, "at_grpo_surrogate_from_logp")
     return dict(loss=loss, clip_mask=clip_mask, n_valid=n_valid, workspace=ws)
+
+
+def at_grpo_surrogate_diagnostics(batch: Batch, logp, old_logp, adv, eps_low: float, eps_high: float):
+    """Returns dict(counts int32[n_heads, 4] (rows, below, above, zero-gradient),
+    stats float32[n_heads, 2] (KL estimate, mean ratio), workspace)."""
+    lib = load_library()
+    cb = batch.to_c()
+    _dev_check(logp, old_logp, adv)
+    dev = logp.device
+    counts = torch.empty((cb.n_heads, 4), dtype=torch.int32, device=dev)
+    stats = torch.empty((cb.n_heads, 2), dtype=torch.float32, device=dev)
+    ws = _workspace(lib.at_grpo_workspace_bytes(CALL_DIAGNOSTICS, C.byref(cb), 0, 0, 0, 0), dev)
+    st = lib.at_grpo_surrogate_diagnostics(C.byref(cb), _ptr(logp), _ptr(old_logp), _ptr(adv), eps_low, eps_high,
+                                           _ptr(counts), _ptr(stats), _ptr(ws), ws.numel(), _stream())
+    _check(st, "at_grpo_surrogate_diagnostics")
+    return dict(counts=counts, stats=stats, workspace=ws)
 
 
 def at_grpo_policy_loss_fwd(batch: Batch, old_logp, adv, eps_low: float, eps_high: float,

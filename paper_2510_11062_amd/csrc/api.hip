@@ -190,6 +190,10 @@ extern "C" size_t at_grpo_workspace_bytes(int32_t which_call, const at_grpo_batc
   if (which_call == AT_GRPO_CALL_GROUP_ADVANTAGE)
     return group_advantage_workspace(n_resp, n_env, n_agent, n_turn);
   if (which_call == AT_GRPO_CALL_HEAD_UPDATE) return head_update_workspace();
+  if (which_call == AT_GRPO_CALL_DIAGNOSTICS) {
+    if (check_layout(batch, false) != AT_GRPO_OK) return 0;
+    return diagnostics_workspace(batch->n_resp);
+  }
   if (which_call < AT_GRPO_CALL_TOKEN_LOGPROB || which_call > AT_GRPO_CALL_SURROGATE) return 0;
   const bool tensors = which_call != AT_GRPO_CALL_SURROGATE;
   if (check_layout(batch, tensors) != AT_GRPO_OK) return 0;
@@ -227,6 +231,22 @@ extern "C" int at_grpo_surrogate_from_logp(const at_grpo_batch* batch, const flo
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   ATG_TRY(launch_fill_i32(p.S.err, 1, 0, s));
   return launch_surrogate(p.L, p.S, logp, old_logp, adv, eps_low, eps_high, agg, loss, clip_mask, n_valid, s);
+}
+
+extern "C" int at_grpo_surrogate_diagnostics(const at_grpo_batch* batch, const float* logp,
+                                             const float* old_logp, const float* adv, float eps_low,
+                                             float eps_high, int32_t* counts, float* stats, void* workspace,
+                                             size_t workspace_bytes, void* hip_stream) {
+  ATG_TRY(check_layout(batch, false));
+  ATG_TRY(check_pointers(batch, false));
+  if (!logp || !old_logp || !adv || !counts || !stats) return AT_GRPO_EINVAL;
+  if (!eps_ok(eps_low, eps_high)) return AT_GRPO_EINVAL;
+  ATG_TRY(check_workspace(workspace, workspace_bytes, diagnostics_workspace(batch->n_resp)));
+  WsAlloc ws(nullptr);
+  Plan p{};
+  make_plan(batch, AT_GRPO_CALL_SURROGATE, ws, &p);   // layout only; the scratch is laid out by the launcher
+  return launch_diagnostics(p.L, logp, old_logp, adv, eps_low, eps_high, counts, stats, workspace,
+                            static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" int at_grpo_policy_loss_fwd(const at_grpo_batch* batch, const float* old_logp, const float* adv,

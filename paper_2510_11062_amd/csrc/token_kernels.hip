@@ -330,6 +330,119 @@ __global__ __launch_bounds__(1024) void k_loss_final(int n_resp, const float* __
   }
 }
 
+// Diagnostics of the clipped-ratio update, one wavefront per response: participating rows, rows below
+// / above the clip range, rows on the clipped branch, and the sums of ratio - 1 - d and of the ratio.
+struct DiagPartials {
+  int32_t* head;    // [n_resp]
+  int32_t* n;       // [n_resp] x 4: rows, low, high, zero-gradient (struct of arrays)
+  int32_t* low;
+  int32_t* high;
+  int32_t* zero;
+  float* kl;        // [n_resp]
+  float* ratio;     // [n_resp]
+};
+
+__global__ __launch_bounds__(256) void k_diag_resp(TokenLayout L, const float* __restrict__ logp,
+                                                   const float* __restrict__ old_logp,
+                                                   const float* __restrict__ adv, ClipConst cc, DiagPartials P,
+                                                   int32_t* __restrict__ err) {
+  const int lane = threadIdx.x & 63;
+  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int n_waves = (gridDim.x * blockDim.x) >> 6;
+  for (int r = wave; r < L.n_resp; r += n_waves) {
+    const int64_t lo = L.cu_seqlens[r], hi = L.cu_seqlens[r + 1];
+    int head = -1;
+    int n = 0, low = 0, high = 0, zero = 0;
+    float kl = 0.f, rs = 0.f;
+    if (lo < 0 || hi < lo || hi > L.n_tok) {
+      if (lane == 0) atomicOr(err, AT_GRPO_DATA_SEQLENS);
+    } else {
+      head = head_of_response(r, L.n_heads, L.n_agent, L.resp_agent, L.head_of_agent, err);
+      const float A = adv[r];
+      for (int64_t t = lo + lane; t < hi; t += 64) {
+        bool on = (head >= 0) && (L.mask == nullptr || L.mask[t] != 0);
+        if (on && L.token_id != nullptr) {
+          const int y = L.token_id[t];
+          if (y < 0 || y >= L.V) {
+            atomicOr(err, AT_GRPO_DATA_TOKEN_RANGE);
+            on = false;
+          }
+        }
+        if (on) {
+          const float d = logp[t] - old_logp[t];
+          const bool is_low = d < cc.lo, is_high = d > cc.hi;
+          ++n;
+          low += is_low;
+          high += is_high;
+          zero += (is_high && A > 0.f) || (is_low && A < 0.f);
+          kl += expm1f(d) - d;
+          rs += expf(d);
+        }
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      n += __shfl_xor(n, o, 64);
+      low += __shfl_xor(low, o, 64);
+      high += __shfl_xor(high, o, 64);
+      zero += __shfl_xor(zero, o, 64);
+      kl += __shfl_xor(kl, o, 64);
+      rs += __shfl_xor(rs, o, 64);
+    }
+    if (lane == 0) {
+      P.head[r] = head;
+      P.n[r] = n;
+      P.low[r] = low;
+      P.high[r] = high;
+      P.zero[r] = zero;
+      P.kl[r] = kl;
+      P.ratio[r] = rs;
+    }
+  }
+}
+
+// one 1024-thread block per head: fixed-order sums of the per-response partials
+__global__ __launch_bounds__(1024) void k_diag_final(int n_resp, DiagPartials P, int32_t* __restrict__ counts,
+                                                     float* __restrict__ stats) {
+  __shared__ int is[4][16];
+  __shared__ float fs[2][16];
+  const int m = blockIdx.x;
+  int c[4] = {0, 0, 0, 0};
+  float f[2] = {0.f, 0.f};
+  for (int r = threadIdx.x; r < n_resp; r += 1024) {
+    if (P.head[r] != m) continue;
+    c[0] += P.n[r];
+    c[1] += P.low[r];
+    c[2] += P.high[r];
+    c[3] += P.zero[r];
+    f[0] += P.kl[r];
+    f[1] += P.ratio[r];
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    c[k] = wave_sum_int(c[k]);
+    if (lane == 0) is[k][wave] = c[k];
+  }
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    f[k] = wave_sum(f[k]);
+    if (lane == 0) fs[k][wave] = f[k];
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int tot[4] = {0, 0, 0, 0};
+    float ft[2] = {0.f, 0.f};
+    for (int w = 0; w < 16; ++w) {
+      for (int k = 0; k < 4; ++k) tot[k] += is[k][w];
+      for (int k = 0; k < 2; ++k) ft[k] += fs[k][w];
+    }
+    for (int k = 0; k < 4; ++k) counts[m * 4 + k] = tot[k];
+    stats[m * 2 + 0] = tot[0] > 0 ? ft[0] / static_cast<float>(tot[0]) : 0.f;
+    stats[m * 2 + 1] = tot[0] > 0 ? ft[1] / static_cast<float>(tot[0]) : 0.f;
+  }
+}
+
 __global__ __launch_bounds__(256) void k_coef(int64_t n_tok, int32_t* __restrict__ flag,
                                               const int32_t* __restrict__ resp_of_tok,
                                               const int32_t* __restrict__ resp_len,
@@ -465,6 +578,37 @@ int launch_surrogate(const TokenLayout& L, const TokenScratch& S, const float* l
   ATG_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_loss_final, dim3(L.n_heads), dim3(1024), 0, s, L.n_resp, S.resp_sum, S.resp_len,
                      S.resp_head, agg, loss, n_valid);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+size_t diagnostics_workspace(int32_t n_resp) {
+  WsAlloc ws(nullptr);
+  ws.take<int32_t>(64);
+  for (int k = 0; k < 7; ++k) ws.take<int32_t>(static_cast<size_t>(n_resp));
+  return ws.bytes();
+}
+
+int launch_diagnostics(const TokenLayout& L, const float* logp, const float* old_logp, const float* adv,
+                       float eps_low, float eps_high, int32_t* counts, float* stats, void* workspace,
+                       hipStream_t s) {
+  ProfScope ps(PROF_SURROGATE, s);
+  WsAlloc ws(workspace);
+  int32_t* err = ws.take<int32_t>(64);
+  DiagPartials P;
+  P.head = ws.take<int32_t>(static_cast<size_t>(L.n_resp));
+  P.n = ws.take<int32_t>(static_cast<size_t>(L.n_resp));
+  P.low = ws.take<int32_t>(static_cast<size_t>(L.n_resp));
+  P.high = ws.take<int32_t>(static_cast<size_t>(L.n_resp));
+  P.zero = ws.take<int32_t>(static_cast<size_t>(L.n_resp));
+  P.kl = reinterpret_cast<float*>(ws.take<int32_t>(static_cast<size_t>(L.n_resp)));
+  P.ratio = reinterpret_cast<float*>(ws.take<int32_t>(static_cast<size_t>(L.n_resp)));
+  ATG_TRY(launch_fill_i32(err, 1, 0, s));
+  const ClipConst cc = make_clip(eps_low, eps_high);
+  hipLaunchKernelGGL(k_diag_resp, dim3(grid_for(L.n_resp, 4, 16384)), dim3(256), 0, s, L, logp, old_logp, adv, cc,
+                     P, err);
+  ATG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_diag_final, dim3(L.n_heads), dim3(1024), 0, s, L.n_resp, P, counts, stats);
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }

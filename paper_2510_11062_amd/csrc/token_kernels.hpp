@@ -53,6 +53,14 @@ int launch_surrogate(const TokenLayout& L, const TokenScratch& S, const float* l
                      const float* old_logp, const float* adv, float eps_low, float eps_high, int agg,
                      float* loss, uint8_t* clip_mask, int32_t* n_valid, hipStream_t s);
 
+// Diagnostics of the clipped-ratio update: counts[n_heads][4] = (rows, below, above, zero-gradient),
+// stats[n_heads][2] = (mean of ratio - 1 - d, mean ratio).  Self-contained like launch_surrogate; its
+// scratch (an error word and seven per-response arrays) is taken from `workspace`.
+size_t diagnostics_workspace(int32_t n_resp);
+int launch_diagnostics(const TokenLayout& L, const float* logp, const float* old_logp, const float* adv,
+                       float eps_low, float eps_high, int32_t* counts, float* stats, void* workspace,
+                       hipStream_t s);
+
 // Backward coefficient coef[t] = d loss / d logp_t; rewrites flag to -1 where coef == 0.
 int launch_coef(const TokenLayout& L, const TokenScratch& S, const float* logp, const float* old_logp,
                 const float* adv, float eps_low, float eps_high, int agg, const float* grad_loss,

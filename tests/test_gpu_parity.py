@@ -75,6 +75,8 @@ def test_workspace_query_and_argument_errors_on_host():
     assert lib.at_grpo_head_update(0, 64, 64, 1, one, None, one, one, one, opt, 256, None, 0, None) == 1
     opt.step = 1
     assert lib.at_grpo_head_update(0, 64, 64, 1, one, None, one, one, one, opt, 256, None, 0, None) == 3
+    assert lib.at_grpo_workspace_bytes(api.CALL_DIAGNOSTICS, b, 0, 0, 0, 0) > 7 * 4 * 1024
+    assert lib.at_grpo_surrogate_diagnostics(b, None, None, None, 0.2, 0.2, None, None, None, 0, None) == 1
 
 
 # ---------------------------------------------------------------------------- S1 + S2
@@ -398,6 +400,45 @@ def test_surrogate_stage_is_bit_exact_on_masks(gpu_device, name, agg):
     again = api.at_grpo_surrogate_from_logp(dc.layout_only(), torch.from_numpy(logp32).to(gpu_device),
                                             dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip, agg)
     assert torch.equal(again["loss"], out["loss"])            # fixed-order reduction
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["C1", "C3", "C5"])
+def test_surrogate_diagnostics_match_oracle(gpu_device, name):
+    """Clip counts are integers: exact given identical log-probs.  KL estimate and mean ratio to fp32
+    accuracy.  Two calls give identical bits (fixed-order sums)."""
+    cfg = replace(mini_cfg(name), H=64, V=256, name=name + "-diag")
+    if name == "C3":
+        cfg = replace(cfg, E=16, len_lo=40, len_hi=300, padded=True)
+    if name == "C5":
+        cfg = replace(cfg, E=8, len_lo=1, len_hi=90)
+    c = helpers.build_case(cfg)
+    c.old_logp = (c.old_logp + 2 * c.noise).astype(np.float32)
+    on = helpers.oracle_fwd(c)
+    logp32 = on["logp"].astype(np.float32)
+    counts, kl, ratio = orc.surrogate_diagnostics(logp32, c.old_logp, c.adv, c.st.mask, on["head_of_tok"],
+                                                  on["resp_of_tok"], cfg.n_heads, cfg.eps_clip, cfg.eps_clip)
+    dc = DeviceCase(c, gpu_device)
+    say(f"[diagnostics] {cfg.name} rows={c.st.n_tok} heads={cfg.n_heads}")
+    out = api.at_grpo_surrogate_diagnostics(dc.layout_only(), torch.from_numpy(logp32).to(gpu_device), dc.old_logp,
+                                            dc.adv, cfg.eps_clip, cfg.eps_clip)
+    torch.cuda.synchronize()
+    assert api.error_word(out["workspace"]) == 0
+    assert np.array_equal(host(out["counts"]).astype(np.int64), counts)
+    assert counts[:, 1].sum() > 0 and counts[:, 2].sum() > 0 and counts[:, 3].sum() > 0
+    stats = host(out["stats"]).astype(np.float64)
+    assert np.allclose(stats[:, 0], kl, rtol=1e-4, atol=1e-7)
+    assert np.allclose(stats[:, 1], ratio, rtol=1e-5, atol=0)
+    again = api.at_grpo_surrogate_diagnostics(dc.layout_only(), torch.from_numpy(logp32).to(gpu_device),
+                                              dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip)
+    assert torch.equal(again["stats"], out["stats"]) and torch.equal(again["counts"], out["counts"])
+    # the counts are the bit counts of the clip mask the surrogate stage writes
+    sur = api.at_grpo_surrogate_from_logp(dc.layout_only(), torch.from_numpy(logp32).to(gpu_device), dc.old_logp,
+                                          dc.adv, cfg.eps_clip, cfg.eps_clip)
+    torch.cuda.synchronize()
+    cm = host(sur["clip_mask"])
+    assert [(cm & b != 0).sum() for b in (1, 2, 4)] == counts[:, 1:].sum(axis=0).tolist()
+    assert host(sur["n_valid"]).tolist() == counts[:, 0].tolist()
 
 
 @pytest.mark.gpu
