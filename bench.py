@@ -29,14 +29,17 @@ CHUNK_TOKENS = 32768                       # list positions one head-kernel laun
 KERNEL_SYMBOL = {"head_fwd": "k_head_fwd", "head_dz": "k_head_dz", "head_dh": "k_head_dh", "head_dw": "k_head_dw"}
 
 
+HEAD_KERNEL_SOURCES = ("common.hpp", "gemm_core.hpp", "head_kernels.hpp", "head_kernels.hip")
+
+
 def kernel_source_digest():
-    """sha256 over the HIP sources: HBM counter readings are only quoted for the code they were taken on."""
+    """sha256 over the sources of the head kernels (the ones `traffic` is quoted for): HBM counter
+    readings are only reported for the code they were taken on."""
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2510_11062_amd", "csrc")
-    for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".hpp")):
-            h.update(open(os.path.join(csrc, name), "rb").read())
+    for name in HEAD_KERNEL_SOURCES:
+        h.update(open(os.path.join(csrc, name), "rb").read())
     return h.hexdigest()
 
 
