@@ -27,9 +27,9 @@ class DeviceCase:
         self.resp_agent = i32(st.agent_id) if multi else None
         self.head_of_agent = i32(st.head_of_agent) if multi else None
 
-    def batch(self):
-        return api.Batch(self.hidden, self.W, self.token_id, self.cu, self.mask, self.resp_agent,
-                         self.head_of_agent)
+    def batch(self, W=None):
+        return api.Batch(self.hidden, self.W if W is None else W, self.token_id, self.cu, self.mask,
+                         self.resp_agent, self.head_of_agent)
 
     def layout_only(self):
         return api.Batch(None, None, self.token_id, self.cu, self.mask, self.resp_agent, self.head_of_agent,
