@@ -72,7 +72,19 @@ def main():
             "write_bytes_per_launch": w_k[sym]["bytes_per_launch"],
             "hbm_bytes_per_launch": f_k[sym]["bytes_per_launch"] + w_k[sym]["bytes_per_launch"],
         }
-    rec = {"workload": workload, "source_digest": bench.kernel_source_digest(),
+    commands = [
+        "cd /tmp && export TMPDIR=/tmp",
+        f"rocprofv3 --pmc FETCH_SIZE -d <out>/pmc_fetch -o f --output-format csv -- python3 bench.py --config {workload} "
+        "--steps 1 --warmup 0 --cpu-sample 0 --calibration-copy",
+        f"rocprofv3 --pmc WRITE_SIZE -d <out>/pmc_write -o w --output-format csv -- python3 bench.py --config {workload} "
+        "--steps 1 --warmup 0 --cpu-sample 0 --calibration-copy",
+        f"python3 -m paper_2510_11062_amd.traffic_from_pmc <out>/pmc_fetch/f_counter_collection.csv "
+        f"<out>/pmc_write/w_counter_collection.csv {workload} profiles/hbm_traffic_{workload}.txt",
+    ]
+    rec = {"what": "bytes between L2 and the memory fabric per launch of each head kernel (launches with rows "
+                   "only), from rocprofv3 counters scaled by a 1 GiB copy in the same run",
+           "commands": commands,
+           "workload": workload, "source_digest": bench.kernel_source_digest(),
            "calibration": {"copy_bytes_each_way": GIB, "FETCH_SIZE_reading": f_cal, "bytes_per_FETCH_SIZE_unit": f_scale,
                            "WRITE_SIZE_reading": w_cal, "bytes_per_WRITE_SIZE_unit": w_scale},
            "kernels": kernels}
