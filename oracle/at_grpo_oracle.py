@@ -208,6 +208,29 @@ def token_logprob(hidden, W_list, token_id, mask, head_of_tok):
     return logp, lse
 
 
+def token_entropy_single(hidden, W):
+    """Entropy of the policy's next-token distribution at every row, H = - sum_v p_v ln p_v with
+    p = softmax(hidden W^T), under ONE head (a monitor: the paper's entropy coefficient is 0)."""
+    z = head_logits(hidden, W)
+    z = z - z.max(axis=1, keepdims=True)
+    e = np.exp(z)
+    p = e / e.sum(axis=1, keepdims=True)
+    logp = np.where(p > 0, np.log(np.where(p > 0, p, 1.0)), 0.0)
+    return -(p * logp).sum(axis=1)
+
+
+def token_entropy(hidden, W_list, mask, head_of_tok):
+    """Entropy for every row; rows with mask 0 (or owned by no response) give 0."""
+    n_tok = np.asarray(hidden).shape[0]
+    m = np.ones(n_tok, dtype=bool) if mask is None else (np.asarray(mask) != 0)
+    ent = np.zeros(n_tok, dtype=np.float64)
+    for k, W in enumerate(W_list):
+        rows = np.nonzero(m & (head_of_tok == k))[0]
+        if rows.size:
+            ent[rows] = token_entropy_single(np.asarray(hidden)[rows], W)
+    return ent
+
+
 # --------------------------------------------------------------------------------------
 # S5 + S6: clipped surrogate and masked averaging  (Eq. 2)
 # --------------------------------------------------------------------------------------

@@ -684,3 +684,46 @@ def test_diagnostics_counts_follow_the_clip_truth_table_and_kl_is_nonnegative():
         assert counts[k, 3] == sum((d32[t] > np.float32(hi) and adv[t] > 0) or (d32[t] < np.float32(lo) and adv[t] < 0)
                                    for t in rows)
         assert math.isclose(ratio[k], sum(math.exp(d32[t]) for t in rows) / len(rows), rel_tol=1e-12)
+
+
+# ----------------------------------------------------------------------------------------
+# entropy of the next-token distribution (monitor)
+# ----------------------------------------------------------------------------------------
+def test_entropy_closed_forms_and_library_routine():
+    from scipy.stats import entropy as scipy_entropy
+    rng = np.random.default_rng(21)
+    # zero head: uniform distribution, H = ln V (golden values used for the log-softmax too)
+    h = rng.standard_normal((3, 8))
+    assert np.allclose(orc.token_entropy_single(h, np.zeros((512, 8))), math.log(512), rtol=1e-14)
+    # two tokens with logits (a, 0): the binary entropy of sigmoid(a)
+    a = 1.7
+    H = orc.token_entropy_single(np.array([[1.0]]), np.array([[a], [0.0]]))[0]
+    q = 1 / (1 + math.exp(-a))
+    assert math.isclose(H, -(q * math.log(q) + (1 - q) * math.log(1 - q)), rel_tol=1e-13)
+    # a library routine on explicit probabilities; bounds; shift invariance; a peaked row tends to 0
+    W = rng.standard_normal((40, 8))
+    z = h @ W.T
+    p = np.exp(z - z.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    got = orc.token_entropy_single(h, W)
+    assert np.allclose(got, [scipy_entropy(row) for row in p], rtol=1e-12)
+    assert np.all(got > 0) and np.all(got < math.log(40))
+    u = rng.standard_normal(8)
+    assert np.allclose(orc.token_entropy_single(h, W + u[None, :]), got, rtol=1e-10)
+    assert orc.token_entropy_single(h[:1] * 1e3, W)[0] < 1e-6
+    # identity with the quantities of the forward: H = lse - E_p[z]
+    logp_all = z - (z.max(axis=1, keepdims=True) + np.log(np.exp(z - z.max(axis=1, keepdims=True)).sum(axis=1, keepdims=True)))
+    lse = orc.token_logprob_single(h, W, np.zeros(3, dtype=np.int64))[1]
+    assert np.allclose(got, lse - (np.exp(logp_all) * z).sum(axis=1), rtol=1e-12)
+
+
+def test_entropy_routing_and_mask():
+    rng = np.random.default_rng(22)
+    h = rng.standard_normal((6, 4))
+    Ws = [rng.standard_normal((9, 4)), rng.standard_normal((9, 4))]
+    head = np.array([0, 1, 1, -1, 0, 1])
+    mask = np.array([1, 1, 0, 1, 1, 1], dtype=np.uint8)
+    ent = orc.token_entropy(h, Ws, mask, head)
+    assert ent[2] == 0 and ent[3] == 0
+    assert np.allclose(ent[[0, 4]], orc.token_entropy_single(h[[0, 4]], Ws[0]))
+    assert np.allclose(ent[[1, 5]], orc.token_entropy_single(h[[1, 5]], Ws[1]))
