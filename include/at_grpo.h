@@ -75,7 +75,8 @@ typedef enum {
   AT_GRPO_CALL_POLICY_LOSS_BWD = 3,
   AT_GRPO_CALL_SURROGATE = 4,
   AT_GRPO_CALL_HEAD_UPDATE = 5,  /* size does not depend on the other arguments */
-  AT_GRPO_CALL_DIAGNOSTICS = 6
+  AT_GRPO_CALL_DIAGNOSTICS = 6,
+  AT_GRPO_CALL_TOKEN_ENTROPY = 7
 } at_grpo_call;
 
 /*
@@ -171,6 +172,17 @@ int at_grpo_surrogate_from_logp(const at_grpo_batch* batch, const float* logp, c
                                 const float* adv, float eps_low, float eps_high, int32_t agg,
                                 float* loss, uint8_t* clip_mask, int32_t* n_valid,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * at_grpo_token_logprob plus a monitor: the entropy of the next-token distribution at every
+ * participating row, H_t = - sum_v p_v ln p_v = lse_t - sum_v p_v z_v, from one more partial sum per
+ * vocabulary tile in the same pass (the paper trains with entropy coefficient 0, App. C.1; nothing in
+ * the loss uses it).  Rows that take no part get 0.
+ *   logp[n_tok], lse[n_tok] (may be NULL), entropy[n_tok]
+ * Workspace: AT_GRPO_CALL_TOKEN_ENTROPY.
+ */
+int at_grpo_token_entropy(const at_grpo_batch* batch, float* logp, float* lse, float* entropy,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Monitors of the clipped-ratio update of Eq. (2), per policy, over the same participating rows as

@@ -20,12 +20,12 @@ _lib = None
 AGG = {"token_mean": 0, "seq_mean_token_mean": 1}
 NORM = {"std": 0, "none": 1}
 CALL_GROUP_ADVANTAGE, CALL_TOKEN_LOGPROB, CALL_POLICY_LOSS_FWD, CALL_POLICY_LOSS_BWD, CALL_SURROGATE, \
-    CALL_HEAD_UPDATE, CALL_DIAGNOSTICS = range(7)
+    CALL_HEAD_UPDATE, CALL_DIAGNOSTICS, CALL_TOKEN_ENTROPY = range(8)
 DTYPE = {torch.float32: 0, torch.bfloat16: 1}
 
 EXPORTS = [
     "at_grpo_group_advantage", "at_grpo_group_advantage_mixed", "at_grpo_token_logprob", "at_grpo_surrogate_from_logp",
-    "at_grpo_surrogate_diagnostics",
+    "at_grpo_surrogate_diagnostics", "at_grpo_token_entropy",
     "at_grpo_policy_loss_fwd", "at_grpo_policy_loss_bwd", "at_grpo_head_update", "at_grpo_workspace_bytes",
     "at_grpo_status_string", "at_grpo_version", "at_grpo_profile_enable", "at_grpo_profile_classes",
     "at_grpo_profile_read",
@@ -77,6 +77,8 @@ def load_library():
     lib.at_grpo_surrogate_from_logp.argtypes = [C.POINTER(_Batch), vp, vp, vp, f32, f32, i32, vp, vp, vp,
                                                 vp, sz, vp]
     lib.at_grpo_surrogate_from_logp.restype = C.c_int
+    lib.at_grpo_token_entropy.argtypes = [C.POINTER(_Batch), vp, vp, vp, vp, sz, vp]
+    lib.at_grpo_token_entropy.restype = C.c_int
     lib.at_grpo_surrogate_diagnostics.argtypes = [C.POINTER(_Batch), vp, vp, vp, f32, f32, vp, vp, vp, sz, vp]
     lib.at_grpo_surrogate_diagnostics.restype = C.c_int
     lib.at_grpo_policy_loss_fwd.argtypes = [C.POINTER(_Batch), vp, vp, f32, f32, i32, vp, vp, vp, vp, vp,
@@ -309,6 +311,20 @@ def at_grpo_token_logprob(batch: Batch, want_lse: bool = True):
     st = lib.at_grpo_token_logprob(C.byref(cb), _ptr(logp), _ptr(lse), _ptr(ws), ws.numel(), _stream())
     _check(st, "at_grpo_token_logprob")
     return dict(logp=logp, lse=lse, workspace=ws)
+
+
+def at_grpo_token_entropy(batch: Batch):
+    """logp, lse and the entropy of the next-token distribution at every participating row."""
+    lib = load_library()
+    cb = batch.to_c()
+    dev = batch.hidden.device
+    logp = torch.empty(cb.n_tok, dtype=torch.float32, device=dev)
+    lse = torch.empty(cb.n_tok, dtype=torch.float32, device=dev)
+    entropy = torch.empty(cb.n_tok, dtype=torch.float32, device=dev)
+    ws = _workspace(lib.at_grpo_workspace_bytes(CALL_TOKEN_ENTROPY, C.byref(cb), 0, 0, 0, 0), dev)
+    st = lib.at_grpo_token_entropy(C.byref(cb), _ptr(logp), _ptr(lse), _ptr(entropy), _ptr(ws), ws.numel(), _stream())
+    _check(st, "at_grpo_token_entropy")
+    return dict(logp=logp, lse=lse, entropy=entropy, workspace=ws)
 
 
 def at_grpo_surrogate_from_logp(batch: Batch, logp, old_logp, adv, eps_low: float, eps_high: float,

@@ -60,6 +60,7 @@ struct Plan {
   int n_chunks;      // super-chunks per head in the worst case (all rows on one head)
   float* part_m;
   float* part_s;
+  float* part_u;     // entropy call only
   float* zy;
   float* coef;
   void* Wt;
@@ -143,10 +144,12 @@ void make_plan(const at_grpo_batch* b, int call, WsAlloc& ws, Plan* p) {
   g.TC = static_cast<int>(tc);
   p->n_chunks = static_cast<int>(ceil_div(n_tok, tc));
 
-  if (call == AT_GRPO_CALL_TOKEN_LOGPROB || call == AT_GRPO_CALL_POLICY_LOSS_FWD) {
+  if (call == AT_GRPO_CALL_TOKEN_LOGPROB || call == AT_GRPO_CALL_POLICY_LOSS_FWD ||
+      call == AT_GRPO_CALL_TOKEN_ENTROPY) {
     const size_t np = static_cast<size_t>(g.n_vtiles) * static_cast<size_t>(g.TC);
     p->part_m = ws.take<float>(np);
     p->part_s = ws.take<float>(np);
+    p->part_u = call == AT_GRPO_CALL_TOKEN_ENTROPY ? ws.take<float>(np) : nullptr;
     p->zy = ws.take<float>(static_cast<size_t>(g.TC));
   }
   if (call == AT_GRPO_CALL_POLICY_LOSS_BWD) {
@@ -163,15 +166,18 @@ int check_workspace(void* workspace, size_t have, size_t need) {
   return AT_GRPO_OK;
 }
 
-int enqueue_logprob(const at_grpo_batch* b, const Plan& p, float* logp, float* lse, hipStream_t s) {
+int enqueue_logprob(const at_grpo_batch* b, const Plan& p, float* logp, float* lse, float* entropy,
+                    hipStream_t s) {
   ATG_TRY(launch_route(p.L, p.S, s));
   ATG_TRY(launch_compact(p.L, p.S, true, s));
   ATG_TRY(launch_zero_nonparticipating(p.L, p.S, logp, lse, s));
+  if (entropy) ATG_TRY(launch_zero_nonparticipating(p.L, p.S, entropy, nullptr, s));
+  float* part_u = entropy ? p.part_u : nullptr;
   for (int m = 0; m < b->n_heads; ++m) {
     for (int c = 0; c < p.n_chunks; ++c) {
       const HeadChunk ch{p.S.idx + static_cast<size_t>(m) * p.L.n_tok, p.S.cnt + m, c * p.g.TC};
-      ATG_TRY(launch_head_fwd(p.g, ch, b->hidden, b->W[m], b->token_id, p.part_m, p.part_s, p.zy, s));
-      ATG_TRY(launch_lse_combine(p.g, ch, p.part_m, p.part_s, p.zy, logp, lse, s));
+      ATG_TRY(launch_head_fwd(p.g, ch, b->hidden, b->W[m], b->token_id, p.part_m, p.part_s, part_u, p.zy, s));
+      ATG_TRY(launch_lse_combine(p.g, ch, p.part_m, p.part_s, part_u, p.zy, logp, lse, entropy, s));
     }
   }
   return AT_GRPO_OK;
@@ -194,7 +200,9 @@ extern "C" size_t at_grpo_workspace_bytes(int32_t which_call, const at_grpo_batc
     if (check_layout(batch, false) != AT_GRPO_OK) return 0;
     return diagnostics_workspace(batch->n_resp);
   }
-  if (which_call < AT_GRPO_CALL_TOKEN_LOGPROB || which_call > AT_GRPO_CALL_SURROGATE) return 0;
+  if ((which_call < AT_GRPO_CALL_TOKEN_LOGPROB || which_call > AT_GRPO_CALL_SURROGATE) &&
+      which_call != AT_GRPO_CALL_TOKEN_ENTROPY)
+    return 0;
   const bool tensors = which_call != AT_GRPO_CALL_SURROGATE;
   if (check_layout(batch, tensors) != AT_GRPO_OK) return 0;
   WsAlloc ws(nullptr);
@@ -212,7 +220,19 @@ extern "C" int at_grpo_token_logprob(const at_grpo_batch* batch, float* logp, fl
   Plan p{};
   make_plan(batch, AT_GRPO_CALL_TOKEN_LOGPROB, ws, &p);
   ATG_TRY(check_workspace(workspace, workspace_bytes, ws.bytes()));
-  return enqueue_logprob(batch, p, logp, lse, static_cast<hipStream_t>(hip_stream));
+  return enqueue_logprob(batch, p, logp, lse, nullptr, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int at_grpo_token_entropy(const at_grpo_batch* batch, float* logp, float* lse, float* entropy,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  ATG_TRY(check_layout(batch, true));
+  ATG_TRY(check_pointers(batch, true));
+  if (!logp || !entropy) return AT_GRPO_EINVAL;
+  WsAlloc ws(workspace);
+  Plan p{};
+  make_plan(batch, AT_GRPO_CALL_TOKEN_ENTROPY, ws, &p);
+  ATG_TRY(check_workspace(workspace, workspace_bytes, ws.bytes()));
+  return enqueue_logprob(batch, p, logp, lse, entropy, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" int at_grpo_surrogate_from_logp(const at_grpo_batch* batch, const float* logp,
@@ -262,7 +282,7 @@ extern "C" int at_grpo_policy_loss_fwd(const at_grpo_batch* batch, const float* 
   make_plan(batch, AT_GRPO_CALL_POLICY_LOSS_FWD, ws, &p);
   ATG_TRY(check_workspace(workspace, workspace_bytes, ws.bytes()));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  ATG_TRY(enqueue_logprob(batch, p, logp, lse, s));
+  ATG_TRY(enqueue_logprob(batch, p, logp, lse, nullptr, s));
   return launch_surrogate(p.L, p.S, logp, old_logp, adv, eps_low, eps_high, agg, loss, clip_mask, n_valid, s);
 }
 

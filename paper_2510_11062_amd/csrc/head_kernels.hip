@@ -32,12 +32,14 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // ------------------------------------------------------------------------------------------------
 // forward: A = W rows (vocab -> accumulator registers), B = hidden rows (tokens -> lanes)
 // ------------------------------------------------------------------------------------------------
-template <typename T>
+// ENT: also emit part_u, the partial sums of 2^(z log2e - m) * z that the entropy monitor needs
+// (H = lse - E_p[z]); the default instantiation carries none of it.
+template <typename T, bool ENT>
 __global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
     const T* __restrict__ hidden, const T* __restrict__ W, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cnt, int c0, const int32_t* __restrict__ token_id,
-    float* __restrict__ part_m, float* __restrict__ part_s, float* __restrict__ zy, int H, int V,
-    int TC, int n_vtiles) {
+    float* __restrict__ part_m, float* __restrict__ part_s, float* __restrict__ part_u,
+    float* __restrict__ zy, int H, int V, int TC, int n_vtiles) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int n = chunk_count(cnt, c0, TC);
   if (n <= 0) return;
@@ -48,6 +50,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
   const int nk = static_cast<int>(row_bytes / kStepBytes);
   float* red_m = reinterpret_cast<float*>(smem);          // [kWavesA][256]
   float* red_s = red_m + kWavesA * kTile;                 // [kWavesA][256]
+  float* red_u = red_s + kWavesA * kTile;                 // [kWavesA][256], entropy variant only
 
   for (int t = logical_workgroup(); t < total; t += gridDim.x) {
     int vt, tt;
@@ -98,25 +101,35 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
       }
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m2 = (mx == -INFINITY) ? 0.f : mx * kLog2e;
-      float sum = 0.f;
+      float sum = 0.f, usum = 0.f;
       if (!ragged) {
 #pragma unroll
         for (int i = 0; i < kIB; ++i)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[i][j][r], kLog2e, -m2));
+          for (int r = 0; r < 16; ++r) {
+            const float e = fast_exp2(fmaf(acc[i][j][r], kLog2e, -m2));
+            sum += e;
+            if (ENT) usum = fmaf(e, acc[i][j][r], usum);
+          }
       } else {
 #pragma unroll
         for (int i = 0; i < kIB; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int vl = i * 32 + 8 * (r >> 2) + 4 * tc.half + (r & 3);
-            if (vl < vrem) sum += fast_exp2(fmaf(acc[i][j][r], kLog2e, -m2));
+            if (vl < vrem) {
+              const float e = fast_exp2(fmaf(acc[i][j][r], kLog2e, -m2));
+              sum += e;
+              if (ENT) usum = fmaf(e, acc[i][j][r], usum);
+            }
           }
       }
       sum += __shfl_xor(sum, 32, 64);
+      if (ENT) usum += __shfl_xor(usum, 32, 64);
       if (tc.half == 0) {
         red_m[tc.wm * kTile + tc.b_row(j)] = (mx == -INFINITY) ? -INFINITY : m2;
         red_s[tc.wm * kTile + tc.b_row(j)] = sum;
+        if (ENT) red_u[tc.wm * kTile + tc.b_row(j)] = usum;
       }
       // target logit: held by exactly one lane of one wavefront of one tile
       const int rel = ycol[j] - vbase;
@@ -139,14 +152,19 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
       float M = -INFINITY;
 #pragma unroll
       for (int q = 0; q < kWavesA; ++q) M = fmaxf(M, red_m[q * kTile + threadIdx.x]);
-      float S = 0.f;
+      float S = 0.f, U = 0.f;
 #pragma unroll
       for (int q = 0; q < kWavesA; ++q) {
         const float mq = red_m[q * kTile + threadIdx.x];
-        if (mq != -INFINITY) S += red_s[q * kTile + threadIdx.x] * fast_exp2(mq - M);
+        if (mq != -INFINITY) {
+          const float sc = fast_exp2(mq - M);
+          S += red_s[q * kTile + threadIdx.x] * sc;
+          if (ENT) U += red_u[q * kTile + threadIdx.x] * sc;
+        }
       }
       part_m[static_cast<size_t>(vt) * TC + t0 + threadIdx.x] = M;
       part_s[static_cast<size_t>(vt) * TC + t0 + threadIdx.x] = S;
+      if (ENT) part_u[static_cast<size_t>(vt) * TC + t0 + threadIdx.x] = U;
     }
     barrier_lds_only();   // the fold buffers are free again; the stores above need not have landed
   }
@@ -159,37 +177,47 @@ __global__ __launch_bounds__(256) void k_lse_combine(const int32_t* __restrict__
                                                      const int32_t* __restrict__ cnt, int c0, int TC,
                                                      int n_part, const float* __restrict__ part_m,
                                                      const float* __restrict__ part_s,
+                                                     const float* __restrict__ part_u,
                                                      const float* __restrict__ zy,
-                                                     float* __restrict__ logp, float* __restrict__ lse) {
-  __shared__ float sm[4][64], ss[4][64];
+                                                     float* __restrict__ logp, float* __restrict__ lse,
+                                                     float* __restrict__ entropy) {
+  __shared__ float sm[4][64], ss[4][64], su[4][64];
   const int n = chunk_count(cnt, c0, TC);
   const int tx = threadIdx.x & 63, py = threadIdx.x >> 6;
   const int j = blockIdx.x * 64 + tx;
   if (blockIdx.x * 64 >= n) return;
-  float M = -INFINITY, S = 0.f;
+  float M = -INFINITY, S = 0.f, U = 0.f;
   if (j < n) {
     for (int p = py; p < n_part; p += 4) {
       const float m = part_m[static_cast<size_t>(p) * TC + j];
       const float s = part_s[static_cast<size_t>(p) * TC + j];
       if (m == -INFINITY) continue;
       const float Mn = fmaxf(M, m);
-      S = S * fast_exp2(M - Mn) + s * fast_exp2(m - Mn);
+      const float so = fast_exp2(M - Mn), sn = fast_exp2(m - Mn);
+      S = S * so + s * sn;
+      if (part_u) U = U * so + part_u[static_cast<size_t>(p) * TC + j] * sn;
       M = Mn;
     }
   }
   sm[py][tx] = M;
   ss[py][tx] = S;
+  su[py][tx] = U;
   __syncthreads();
   if (py == 0 && j < n) {
     float Mt = fmaxf(fmaxf(sm[0][tx], sm[1][tx]), fmaxf(sm[2][tx], sm[3][tx]));
-    float St = 0.f;
+    float St = 0.f, Ut = 0.f;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      if (sm[q][tx] != -INFINITY) St += ss[q][tx] * fast_exp2(sm[q][tx] - Mt);
+      if (sm[q][tx] != -INFINITY) {
+        const float sc = fast_exp2(sm[q][tx] - Mt);
+        St += ss[q][tx] * sc;
+        Ut += su[q][tx] * sc;
+      }
     const float l = (Mt + __log2f(St)) * kLn2;
     const int row = idx[c0 + j];
     logp[row] = zy[j] - l;
     if (lse) lse[row] = l;
+    if (entropy) entropy[row] = l - Ut / St;     // H = lse - E_p[z]
   }
 }
 
@@ -556,31 +584,39 @@ int gemm_grid() {
 // ================================================================================================
 // launchers
 // ================================================================================================
+template <typename T, bool ENT>
+int launch_head_fwd_t(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
+                      const int32_t* token_id, float* part_m, float* part_s, float* part_u, float* zy,
+                      hipStream_t s) {
+  auto k = k_head_fwd<T, ENT>;
+  ATG_TRY(allow_big_lds(k));
+  hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s, static_cast<const T*>(hidden),
+                     static_cast<const T*>(W), ch.idx, ch.cnt, ch.c0, token_id, part_m, part_s, part_u, zy, g.H,
+                     g.V, g.TC, g.n_vtiles);
+  return AT_GRPO_OK;
+}
+
 int launch_head_fwd(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
-                    const int32_t* token_id, float* part_m, float* part_s, float* zy, hipStream_t s) {
+                    const int32_t* token_id, float* part_m, float* part_s, float* part_u, float* zy,
+                    hipStream_t s) {
   ProfScope ps(PROF_HEAD_FWD, s);
   if (g.dtype == AT_GRPO_BF16) {
-    auto k = k_head_fwd<bf16_t>;
-    ATG_TRY(allow_big_lds(k));
-    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
-                       static_cast<const bf16_t*>(hidden), static_cast<const bf16_t*>(W), ch.idx, ch.cnt,
-                       ch.c0, token_id, part_m, part_s, zy, g.H, g.V, g.TC, g.n_vtiles);
+    if (part_u) ATG_TRY((launch_head_fwd_t<bf16_t, true>(g, ch, hidden, W, token_id, part_m, part_s, part_u, zy, s)));
+    else ATG_TRY((launch_head_fwd_t<bf16_t, false>(g, ch, hidden, W, token_id, part_m, part_s, part_u, zy, s)));
   } else {
-    auto k = k_head_fwd<float>;
-    ATG_TRY(allow_big_lds(k));
-    hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
-                       static_cast<const float*>(hidden), static_cast<const float*>(W), ch.idx, ch.cnt,
-                       ch.c0, token_id, part_m, part_s, zy, g.H, g.V, g.TC, g.n_vtiles);
+    if (part_u) ATG_TRY((launch_head_fwd_t<float, true>(g, ch, hidden, W, token_id, part_m, part_s, part_u, zy, s)));
+    else ATG_TRY((launch_head_fwd_t<float, false>(g, ch, hidden, W, token_id, part_m, part_s, part_u, zy, s)));
   }
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }
 
 int launch_lse_combine(const HeadGeom& g, const HeadChunk& ch, const float* part_m, const float* part_s,
-                       const float* zy, float* logp, float* lse, hipStream_t s) {
+                       const float* part_u, const float* zy, float* logp, float* lse, float* entropy,
+                       hipStream_t s) {
   ProfScope ps(PROF_LSE_COMBINE, s);
   hipLaunchKernelGGL(k_lse_combine, dim3(g.TC / 64), dim3(256), 0, s, ch.idx, ch.cnt, ch.c0, g.TC,
-                     g.n_vtiles, part_m, part_s, zy, logp, lse);
+                     g.n_vtiles, part_m, part_s, part_u, zy, logp, lse, part_u ? entropy : nullptr);
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }

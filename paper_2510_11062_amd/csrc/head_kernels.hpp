@@ -25,14 +25,16 @@ struct HeadChunk {
 
 // part_m / part_s: [n_vtiles][TC] per-(vocabulary tile, token) running max (log2 domain) and
 // sum; zy: [TC] target logit.  hidden / W are the caller's tensors.
+// part_u: null, or [n_vtiles][TC] partial sums for the entropy monitor (selects the kernel variant).
 int launch_head_fwd(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
-                    const int32_t* token_id, float* part_m, float* part_s, float* zy,
+                    const int32_t* token_id, float* part_m, float* part_s, float* part_u, float* zy,
                     hipStream_t s);
 
 // logp[row], lse[row] for the rows of this super-chunk (lse may be null).
+// With part_u, also entropy[row] = lse - E_p[z].
 int launch_lse_combine(const HeadGeom& g, const HeadChunk& ch, const float* part_m,
-                       const float* part_s, const float* zy, float* logp, float* lse,
-                       hipStream_t s);
+                       const float* part_s, const float* part_u, const float* zy, float* logp,
+                       float* lse, float* entropy, hipStream_t s);
 
 // Wt[H][Vp] = W[V][H]^T, zero in the k padding.
 int launch_transpose_w(const HeadGeom& g, const void* W, void* Wt, hipStream_t s);

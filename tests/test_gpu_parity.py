@@ -403,6 +403,33 @@ def test_surrogate_stage_is_bit_exact_on_masks(gpu_device, name, agg):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C5"])
+def test_token_entropy_matches_oracle(gpu_device, name):
+    """Entropy of the next-token distribution from the same pass as the log-probs; the log-probs of
+    this variant are bit-identical to those of the plain call."""
+    cfg = mini_cfg(name)
+    c = helpers.build_case(cfg, device=gpu_device)
+    st = c.st
+    ref = orc.token_entropy(c.hidden, c.W, st.mask, c.head_of_tok)
+    dc = DeviceCase(c, gpu_device)
+    say(f"[entropy] {cfg.name} rows={st.n_tok} V={cfg.V}")
+    out = api.at_grpo_token_entropy(dc.batch())
+    plain = api.at_grpo_token_logprob(dc.batch())
+    torch.cuda.synchronize()
+    assert api.error_word(out["workspace"]) == 0
+    assert torch.equal(out["logp"], plain["logp"]) and torch.equal(out["lse"], plain["lse"])
+    got = host(out["entropy"]).astype(np.float64)
+    tol = tolerances(cfg)
+    if tol["logp_abs"] is not None:
+        assert np.abs(got - ref).max() <= tol["logp_abs"]
+    else:
+        assert (np.abs(got - ref) / np.maximum(np.abs(ref), 1.0)).max() <= tol["logp_rel"]
+    on = ref != 0
+    assert on.any() and np.all(got[~on] == 0)
+    assert np.all(got[on] > 0) and np.all(got[on] <= np.log(cfg.V) + 1e-3)
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("name", ["C1", "C3", "C5"])
 def test_surrogate_diagnostics_match_oracle(gpu_device, name):
     """Clip counts are integers: exact given identical log-probs.  KL estimate and mean ratio to fp32
