@@ -392,10 +392,15 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
 #pragma unroll 4
         for (int it = 0; it < kTile / 16; ++it) {
           const int row = it * 16 + (threadIdx.x >> 5);
+          // two 8-byte reads per lane (rows are only 8-byte aligned); lanes 16 apart would hit the same
+          // banks, so the upper half of each row takes its two halves in the opposite order
           const char* src = smem + row * kDzRowStride + col16 * 16;
+          const int flip = (col16 >> 4) << 3;
+          const uint2 first = *reinterpret_cast<const uint2*>(src + flip);
+          const uint2 second = *reinterpret_cast<const uint2*>(src + (flip ^ 8));
+          const uint2 lo = flip ? second : first;
+          const uint2 hi = flip ? first : second;
           uint4 u;
-          const uint2 lo = *reinterpret_cast<const uint2*>(src);
-          const uint2 hi = *reinterpret_cast<const uint2*>(src + 8);
           u.x = lo.x; u.y = lo.y; u.z = hi.x; u.w = hi.y;
           *reinterpret_cast<uint4*>(reinterpret_cast<char*>(dZ) +
                                     (static_cast<size_t>(t0 + row) * Vp + v0 + col16 * 8) * 2) = u;
