@@ -377,7 +377,7 @@ __global__ __launch_bounds__(256) void k_ga_select(const int32_t* __restrict__ n
 // The whole call in one workgroup, for the sizes a training step actually has (a few thousand
 // groups, a few ten thousand responses): histogram, scans and the key tables live in LDS and the
 // phases are separated by workgroup barriers instead of kernel boundaries, so the call costs one
-// launch instead of nine.  Same arithmetic and the same device functions as the multi-launch path.
+// launch instead of five or seven.  Same arithmetic and the same device functions as the multi-launch path.
 // ------------------------------------------------------------------------------------------------
 constexpr int kSingleThreads = 1024;
 constexpr int kSingleMaxKeys = 8192;     // 3 tables of this many ints in LDS (96 KiB)
