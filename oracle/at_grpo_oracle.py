@@ -393,6 +393,29 @@ def head_backward_single(hidden, W, token_id, g):
     return dZ @ w, dZ.T @ h
 
 
+def head_backward_dw_rows(hidden, W_rows, vocab_ids, token_id, g, lse):
+    """Selected rows of dW for ONE head, from the definition, given the log-sum-exp of every token:
+
+        dW[v, :] = sum_t g_t * (1[y_t = v] - exp(<hidden[t], W[v]> - lse_t)) * hidden[t, :]
+
+    hidden [n, H] are the head's rows, W_rows [len(vocab_ids), H] the head's weight rows W[vocab_ids],
+    g [n] the coefficients, lse [n] the log-sum-exp over the WHOLE vocabulary of each row (an input:
+    a row of dW needs only that one column of the logits).  Costs O(n * H) per requested row, which
+    is what makes single rows of a full-size gradient checkable.  Returns [len(vocab_ids), H] fp64.
+    """
+    h = np.asarray(hidden, dtype=np.float64)
+    w = np.asarray(W_rows, dtype=np.float64)
+    v = np.asarray(vocab_ids, dtype=np.int64)
+    y = np.asarray(token_id, dtype=np.int64)
+    gg = np.asarray(g, dtype=np.float64)
+    ls = np.asarray(lse, dtype=np.float64)
+    z = h @ w.T                                            # [n, len(v)]: the requested logit columns
+    dZ = -np.exp(z - ls[:, None])
+    dZ += (y[:, None] == v[None, :]).astype(np.float64)
+    dZ *= gg[:, None]
+    return dZ.T @ h
+
+
 def policy_loss_bwd(hidden, W_list, token_id, mask, cu_seqlens, resp_agent, head_of_agent,
                     old_logp, adv, eps_low: float, eps_high: float, agg: str = "token_mean",
                     grad_loss=None):

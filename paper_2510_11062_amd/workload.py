@@ -25,6 +25,7 @@ class DeviceWorkload:
     head_of_tok: torch.Tensor     # int64 [n_tok]
     valid: torch.Tensor           # bool [n_tok]
     noise: Optional[torch.Tensor] = None
+    engine_lse: Optional[torch.Tensor] = None   # the stand-in's log-sum-exp per row (keep_noise only)
 
 
 def build(cfg: synth.RolloutConfig, dev, keep_noise: bool = False) -> DeviceWorkload:
@@ -38,10 +39,12 @@ def build(cfg: synth.RolloutConfig, dev, keep_noise: bool = False) -> DeviceWork
     valid = torch.ones(st.n_tok, dtype=torch.bool, device=dev) if mask is None else mask.bool()
     head_of_resp = torch.from_numpy(st.head_of_agent[st.agent_id].astype(np.int64)).to(dev)
     head_of_tok = head_of_resp[resp_of_tok]
-    token_id, old_logp = rollout_standin.draw_tokens_and_old_logp(hidden, W, head_of_tok, valid, u, noise)
+    drawn = rollout_standin.draw_tokens_and_old_logp(hidden, W, head_of_tok, valid, u, noise, want_lse=keep_noise)
+    token_id, old_logp = drawn[0], drawn[1]
+    engine_lse = drawn[2] if keep_noise else None
     multi = cfg.n_heads > 1
     batch = api.Batch(hidden, W, token_id, cu, mask, i32(st.agent_id) if multi else None,
                       i32(st.head_of_agent) if multi else None)
     return DeviceWorkload(cfg, st, batch, i32(st.env_id), i32(st.agent_id), i32(st.turn_id),
                           torch.from_numpy(st.reward).to(dev), old_logp, resp_of_tok, head_of_tok, valid,
-                          noise if keep_noise else None)
+                          noise if keep_noise else None, engine_lse)

@@ -93,3 +93,41 @@ def rel_fro(a, b):
     b = np.asarray(b, dtype=np.float64)
     den = np.linalg.norm(b)
     return np.linalg.norm(a - b) / (den if den > 0 else 1.0)
+
+
+# ------------------------------------------------------------------------------------------------
+# Gradient comparison.  A Frobenius ratio over a whole matrix hides one wrong row or one wrong tile
+# edge, so gradients are compared row by row and element by element:
+#   row check      max_r ||got_r - ref_r|| / max(||ref_r||, floor)          <= tol
+#   element check  |got - ref| <= tol * |ref| + tol * rms(ref_r)             for every element
+# The element bound carries the row's root-mean-square because an element that is the sum of
+# cancelling terms is only accurate relative to the terms, not to itself.  floor keeps rows that are
+# numerically zero in the reference (far below the typical row) from dividing rounding noise by ~0.
+# ------------------------------------------------------------------------------------------------
+def grad_errors(got, ref, floor_frac=1e-6):
+    """Returns (worst row error, worst element excess, row index of the worst row)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if got.ndim == 1:
+        got, ref = got[None, :], ref[None, :]
+    rn = np.linalg.norm(ref, axis=1)
+    floor = floor_frac * (rn.max() if rn.size else 0.0)
+    row_err = np.linalg.norm(got - ref, axis=1) / np.maximum(np.maximum(rn, floor), 1e-300)
+    rms = rn / np.sqrt(ref.shape[1])
+    # excess[i, j] = |d| / (|ref| + rms_row): compared against tol by the caller
+    den = np.abs(ref) + np.maximum(rms, floor / np.sqrt(ref.shape[1]))[:, None]
+    elem = np.abs(got - ref) / np.maximum(den, 1e-300)
+    worst = int(np.argmax(row_err)) if row_err.size else -1
+    return (float(row_err.max()) if row_err.size else 0.0, float(elem.max()) if elem.size else 0.0, worst)
+
+
+def assert_grad_close(got, ref, tol, what, fro_tol=None):
+    """Row-wise and element-wise gradient parity (see grad_errors), plus the Frobenius bound."""
+    row_err, elem_err, worst = grad_errors(got, ref)
+    fro = rel_fro(got, ref)
+    assert np.all(np.isfinite(np.asarray(got, dtype=np.float64))), f"{what}: non-finite values"
+    assert row_err <= tol, f"{what}: row {worst} off by {row_err:.3e} (tol {tol})"
+    assert elem_err <= tol, f"{what}: an element exceeds tol*(|ref| + rms of its row) by factor {elem_err / tol:.2f}"
+    assert fro <= (tol if fro_tol is None else fro_tol), f"{what}: Frobenius error {fro:.3e}"
+    return row_err, elem_err, fro

@@ -727,3 +727,130 @@ def test_entropy_routing_and_mask():
     assert ent[2] == 0 and ent[3] == 0
     assert np.allclose(ent[[0, 4]], orc.token_entropy_single(h[[0, 4]], Ws[0]))
     assert np.allclose(ent[[1, 5]], orc.token_entropy_single(h[[1, 5]], Ws[1]))
+
+
+# ------------------------------------------------------------------ routing direction, written out by hand
+def test_token_heads_routing_direction_by_hand():
+    """Three agents on two heads with unequal shares: agent 0 -> head 1, agents 1 and 2 -> head 0.
+    Five responses of lengths 2, 0, 3, 1, 2 in a 10-row buffer whose rows 8 and 9 belong to no
+    response.  Expected arrays are typed in, not derived: swapping the heads, or indexing the map
+    by response instead of by agent, changes them."""
+    cu = np.array([0, 2, 2, 5, 6, 8], dtype=np.int64)
+    resp_agent = np.array([0, 2, 1, 0, 2], dtype=np.int32)
+    head_of_agent = np.array([1, 0, 0], dtype=np.int32)
+    resp_of_tok, head_of_tok = orc.token_heads(10, cu, resp_agent, head_of_agent)
+    assert resp_of_tok.tolist() == [0, 0, 2, 2, 2, 3, 4, 4, -1, -1]
+    assert head_of_tok.tolist() == [1, 1, 0, 0, 0, 1, 0, 0, -1, -1]
+    # head 0 owns 5 rows, head 1 owns 3: the token-mean weights follow the same split
+    w, n_valid = orc.token_weights(None, head_of_tok, resp_of_tok, 2, "token_mean")
+    assert n_valid.tolist() == [5, 3]
+    assert w.tolist() == [1 / 3, 1 / 3, 0.2, 0.2, 0.2, 1 / 3, 0.2, 0.2, 0.0, 0.0]
+    # one shared policy: everything on head 0, whatever the agents are
+    _, shared = orc.token_heads(10, cu, None, None)
+    assert shared.tolist() == [0] * 8 + [-1, -1]
+
+
+def test_multi_head_loss_uses_the_head_the_agent_maps_to():
+    """Two heads with very different weights and an asymmetric agent -> head map: the log-prob of a
+    row must be the one under the head its agent maps to, checked against a per-row pure-Python
+    log-softmax that looks the head up itself (no use of token_heads)."""
+    rng = np.random.default_rng(11)
+    H, V = 8, 6
+    cu = np.array([0, 3, 4, 6, 9], dtype=np.int64)
+    resp_agent = np.array([2, 0, 1, 2], dtype=np.int32)
+    head_of_agent = np.array([1, 1, 0], dtype=np.int32)             # agents 0, 1 -> head 1; agent 2 -> head 0
+    hidden = rng.standard_normal((9, H))
+    W = [rng.standard_normal((V, H)), 3.0 * rng.standard_normal((V, H))]
+    y = rng.integers(0, V, size=9)
+    out = orc.policy_loss_fwd(hidden, W, y, None, cu, resp_agent, head_of_agent, np.zeros(9, np.float32),
+                              np.ones(4, np.float32), 0.2, 0.2)
+    for r in range(4):
+        k = int(head_of_agent[int(resp_agent[r])])
+        for t in range(int(cu[r]), int(cu[r + 1])):
+            z = [sum(hidden[t, h] * W[k][v, h] for h in range(H)) for v in range(V)]
+            mx = max(z)
+            lse = mx + math.log(sum(math.exp(a - mx) for a in z))
+            assert out["logp"][t] == pytest.approx(z[int(y[t])] - lse, abs=1e-12)
+    assert out["n_valid"].tolist() == [6, 3]
+
+
+# ------------------------------------------------------------------ single rows of dW
+def test_dw_rows_from_one_logit_column_equal_the_full_backward():
+    """head_backward_dw_rows (one logit column per requested row, log-sum-exp given) against the rows
+    of the full dW, and against a pure-Python triple loop on a tiny case."""
+    c = small_case(n_heads=2)
+    c.old_logp = (c.old_logp + 3 * c.noise).astype(np.float32)
+    out = helpers.oracle_bwd(c)
+    for k in range(2):
+        rows = np.nonzero((out["w"] > 0) & (c.head_of_tok == k))[0]
+        counts = np.bincount(c.token_id[rows], minlength=c.cfg.V)
+        pick = np.unique(np.array([0, c.cfg.V - 1, int(np.argmax(counts)), int(np.argmin(counts)), 7, 8]))
+        got = orc.head_backward_dw_rows(c.hidden[rows], c.W[k][pick], pick, c.token_id[rows], out["g"][rows],
+                                        out["lse"][rows])
+        assert np.allclose(got, out["dW"][k][pick], rtol=1e-12, atol=1e-15)
+    # triple loop, nothing vectorised, lse recomputed from scratch
+    rng = np.random.default_rng(3)
+    n, H, V = 5, 3, 4
+    h, W = rng.standard_normal((n, H)), rng.standard_normal((V, H))
+    y, g = rng.integers(0, V, size=n), rng.standard_normal(n)
+    lse = []
+    for t in range(n):
+        z = [sum(h[t, a] * W[v, a] for a in range(H)) for v in range(V)]
+        lse.append(math.log(sum(math.exp(x) for x in z)))
+    for v in range(V):
+        expect = [0.0] * H
+        for t in range(n):
+            z = sum(h[t, a] * W[v, a] for a in range(H))
+            dz = g[t] * ((1.0 if y[t] == v else 0.0) - math.exp(z - lse[t]))
+            for a in range(H):
+                expect[a] += dz * h[t, a]
+        got = orc.head_backward_dw_rows(h, W[[v]], [v], y, g, lse)[0]
+        assert np.allclose(got, expect, rtol=1e-12, atol=1e-15)
+
+
+# ------------------------------------------------------------------ the gradient comparison itself
+def test_gradient_comparison_catches_planted_mistakes():
+    """The row-wise / element-wise comparison the GPU parity tests use must turn red for the mistakes
+    a chunked backward can make (mistakes are planted in copies of the oracle's own result): a dropped
+    chunk of tokens in dW, a zeroed gradient, one wrong row, one wrong tile edge column, a missed
+    accumulation.  A Frobenius ratio alone lets several of these through."""
+    cfg = replace(synth.CONFIGS["C1"], name="planted", H=16, V=3000, E=16, N=2, T=2, K=4, len_lo=20, len_hi=30,
+                  seed=synth.BASE_SEED + 300, reward_kind="uniform", forced_equal_groups=1)
+    c = helpers.build_case(cfg)
+    out = helpers.oracle_bwd(c)
+    dW, dH = out["dW"][0], out["d_hidden"]
+    tol = 2e-2
+    ok = dW * (1.0 + 1e-3 * np.random.default_rng(0).standard_normal(dW.shape))     # bf16-sized noise passes
+    helpers.assert_grad_close(ok, dW, tol, "noise")
+
+    def fails(bad, ref):
+        with pytest.raises(AssertionError):
+            helpers.assert_grad_close(bad, ref, tol, "planted")
+
+    fails(np.zeros_like(dW), dW)                                   # zeroed gradient
+    rows = np.nonzero(out["w"] > 0)[0]
+    first = rows[: rows.size // 3]                                  # a dropped chunk: only 2/3 of the tokens
+    rest = rows[rows.size // 3:]
+    _, dropped = orc.head_backward_single(c.hidden[rest], c.W[0], c.token_id[rest], out["g"][rest])
+    fails(dropped, dW)
+    one_row = dW.copy()
+    norms = np.linalg.norm(dW, axis=1)
+    light = int(np.argsort(norms)[len(norms) // 10])                # a light (10th percentile) vocabulary row
+    one_row[light] = 0.0                                            # ... lost
+    assert helpers.rel_fro(one_row, dW) < tol                       # ... which the norm alone lets through
+    fails(one_row, dW)
+    edge = dW.copy()
+    edge[-64:, -1] *= 1.5                                           # the last column of the last rows (a tile corner)
+    assert helpers.rel_fro(edge, dW) < tol
+    fails(edge, dW)
+    # accumulation onto an existing gradient is checked as (result - what was there) against dW, with
+    # what was there of dW's own size: an overwrite instead of an add then shows in every element
+    prefill = np.random.default_rng(1).standard_normal(dW.shape) * np.abs(dW).mean()
+    helpers.assert_grad_close((prefill + dW) - prefill, dW, tol, "accumulated")
+    fails(dW - prefill, dW)
+    bad_h = dH.copy()
+    live = np.nonzero(out["g"] != 0)[0]
+    hn = np.linalg.norm(dH[live], axis=1)
+    bad_h[live[int(np.argsort(hn)[len(hn) // 10])]] = 0.0           # one light token row of d_hidden lost
+    assert helpers.rel_fro(bad_h, dH) < tol
+    fails(bad_h, dH)
