@@ -763,7 +763,14 @@ def test_two_mini_batches_accumulate_into_one_update(gpu_device, dtype):
     upd = orc.head_update([W0], [dW_ref], [np.zeros_like(W0)], [np.zeros_like(W0)], 1, **passed)
     assert np.isclose(float(up["grad_norm"][0]), upd["grad_norm"], rtol=tol["grad_rel"])
     move, move_ref = host(stepped).astype(np.float64) - W0, upd["W"][0] - W0
-    # the first Adam step moves every weight by about lr * sign(g): compare the movement itself
-    assert helpers.rel_fro(move, move_ref) <= max(tol["grad_rel"], 1e-3)
+    # The first Adam step moves a weight by lr * g / (|g| + eps), i.e. by about lr * sign(g): it is compared
+    # where the gradient element is not so small against its row that the bf16 rounding of dZ (about 1e-3 of
+    # the row's rms) could turn its sign, and the rest may differ by at most the two steps a flipped sign costs.
+    rms = np.linalg.norm(dW_ref, axis=1, keepdims=True) / np.sqrt(cfg.H)
+    firm = np.abs(dW_ref) > (0.1 if dtype == "bf16" else 1e-3) * rms
+    assert firm.mean() > 0.8
+    assert np.allclose(move[firm], move_ref[firm], rtol=max(tol["grad_rel"], 1e-3), atol=1e-3 * passed["lr"])
+    assert np.abs(move - move_ref).max() <= 2.1 * passed["lr"]
+    assert helpers.rel_fro(move, move_ref) <= 0.1
     if dtype == "bf16":
         assert torch.equal(W[0], master[0].to(torch.bfloat16))
