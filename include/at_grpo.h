@@ -36,7 +36,8 @@ typedef enum {
   AT_GRPO_EINVAL = 1,       /* null pointer, non-positive size, inconsistent arguments */
   AT_GRPO_EUNSUPPORTED = 2, /* dtype / shape the kernels do not cover                 */
   AT_GRPO_EWORKSPACE = 3,   /* workspace missing, misaligned or too small             */
-  AT_GRPO_EHIP = 4          /* a HIP runtime call or kernel launch failed             */
+  AT_GRPO_EHIP = 4,         /* a HIP runtime call or kernel launch failed             */
+  AT_GRPO_ESCRATCH = 5      /* input too large for the library's fixed scratch array  */
 } at_grpo_status;
 
 typedef enum { AT_GRPO_F32 = 0, AT_GRPO_BF16 = 1 } at_grpo_dtype;
@@ -147,6 +148,30 @@ int at_grpo_group_advantage_mixed(int32_t n_resp, int32_t n_env, int32_t n_agent
                                   int32_t* n_groups, int32_t* seg_offsets, int32_t* perm, float* adv,
                                   float* group_mean, float* group_std, int32_t* best, void* workspace,
                                   size_t workspace_bytes, void* hip_stream);
+
+/*
+ * at_grpo_group_advantage for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the scratch
+ * is a fixed array of at_grpo_static_scratch_bytes() bytes (2 MiB) in the library's own device
+ * memory, which every GPU the library runs on holds until the process ends.  The call allocates and
+ * frees nothing.  Same inputs, outputs, arithmetic and results as at_grpo_group_advantage, plus
+ *   data_error[1]  optional device output (NULL to skip): the error word of this call (AT_GRPO_DATA_*)
+ * Limit: at_grpo_workspace_bytes(AT_GRPO_CALL_GROUP_ADVANTAGE, ...) of the same extents must not
+ * exceed at_grpo_static_scratch_bytes(), i.e. about 12 * n_resp + 8 * n_env * n_agent * n_turn bytes
+ * <= 2 MiB (65 536 responses over 65 536 keys fit, as does every workload of the paper's shape); beyond it the call
+ * returns AT_GRPO_ESCRATCH and launches nothing.
+ * All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different streams
+ * or threads) race and must be serialised by the caller.  Everything the kernels need cleared is
+ * cleared by the call itself with fill kernels (no memset nodes), so it may be captured in a graph;
+ * the first call on a device looks the array's address up and should be made outside a capture.
+ */
+size_t at_grpo_static_scratch_bytes(void);
+int at_grpo_group_advantage_static(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn,
+                                   const int32_t* env_id, const int32_t* agent_id, const int32_t* turn_id,
+                                   const float* reward, float eps_std, int32_t ddof, int32_t norm,
+                                   int32_t* group_id, int32_t* n_groups, int32_t* seg_offsets,
+                                   int32_t* perm, float* adv, float* group_mean, float* group_std,
+                                   int32_t* data_error, void* hip_stream);
 
 /*
  * log pi_theta(token_id[t]) and the log-sum-exp of the head logits for every participating row

@@ -24,7 +24,8 @@ CALL_GROUP_ADVANTAGE, CALL_TOKEN_LOGPROB, CALL_POLICY_LOSS_FWD, CALL_POLICY_LOSS
 DTYPE = {torch.float32: 0, torch.bfloat16: 1}
 
 EXPORTS = [
-    "at_grpo_group_advantage", "at_grpo_group_advantage_mixed", "at_grpo_token_logprob", "at_grpo_surrogate_from_logp",
+    "at_grpo_group_advantage", "at_grpo_group_advantage_mixed", "at_grpo_group_advantage_static",
+    "at_grpo_static_scratch_bytes", "at_grpo_token_logprob", "at_grpo_surrogate_from_logp",
     "at_grpo_surrogate_diagnostics", "at_grpo_token_entropy",
     "at_grpo_policy_loss_fwd", "at_grpo_policy_loss_bwd", "at_grpo_head_update", "at_grpo_workspace_bytes",
     "at_grpo_status_string", "at_grpo_version", "at_grpo_profile_enable", "at_grpo_profile_classes",
@@ -72,6 +73,11 @@ def load_library():
     lib.at_grpo_group_advantage_mixed.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, f32, f32, i32, i32,
                                                   vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.at_grpo_group_advantage_mixed.restype = C.c_int
+    lib.at_grpo_group_advantage_static.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, f32, i32, i32,
+                                                   vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.at_grpo_group_advantage_static.restype = C.c_int
+    lib.at_grpo_static_scratch_bytes.argtypes = []
+    lib.at_grpo_static_scratch_bytes.restype = sz
     lib.at_grpo_token_logprob.argtypes = [C.POINTER(_Batch), vp, vp, vp, sz, vp]
     lib.at_grpo_token_logprob.restype = C.c_int
     lib.at_grpo_surrogate_from_logp.argtypes = [C.POINTER(_Batch), vp, vp, vp, f32, f32, i32, vp, vp, vp,
@@ -233,6 +239,45 @@ def at_grpo_group_advantage(env_id, agent_id, turn_id, reward, n_env: int, n_age
                                      _ptr(ws), ws.numel(), _stream())
     _check(st, "at_grpo_group_advantage")
     out["workspace"] = ws
+    return out
+
+
+def group_advantage_outputs(R: int, n_keys: int, dev, want_stats: bool = True):
+    """Output tensors of a grouping call (allocated by the caller, never by the library)."""
+    gmax = min(R, n_keys)
+    return dict(
+        group_id=torch.empty(R, dtype=torch.int32, device=dev),
+        n_groups=torch.zeros(1, dtype=torch.int32, device=dev),
+        seg_offsets=torch.zeros(gmax + 1, dtype=torch.int32, device=dev),
+        perm=torch.zeros(R, dtype=torch.int32, device=dev),
+        adv=torch.empty(R, dtype=torch.float32, device=dev),
+        group_mean=torch.zeros(gmax, dtype=torch.float32, device=dev) if want_stats else None,
+        group_std=torch.zeros(gmax, dtype=torch.float32, device=dev) if want_stats else None,
+        data_error=torch.zeros(1, dtype=torch.int32, device=dev),
+    )
+
+
+def at_grpo_static_scratch_bytes() -> int:
+    return int(load_library().at_grpo_static_scratch_bytes())
+
+
+def at_grpo_group_advantage_static(env_id, agent_id, turn_id, reward, n_env: int, n_agent: int, n_turn: int,
+                                   eps_std: float = 1e-6, ddof: int = 0, norm: str = "std",
+                                   out: Optional[dict] = None):
+    """at_grpo_group_advantage on the library's own fixed scratch array: no workspace is passed and the
+    call allocates nothing (pass `out` from group_advantage_outputs to keep the binding from allocating
+    either).  Returns the dict of outputs, data_error[1] holding the call's error word."""
+    lib = load_library()
+    _dev_check(env_id, agent_id, turn_id, reward)
+    R = reward.numel()
+    if out is None:
+        out = group_advantage_outputs(R, n_env * n_agent * n_turn, reward.device)
+    st = lib.at_grpo_group_advantage_static(R, n_env, n_agent, n_turn, _ptr(env_id), _ptr(agent_id), _ptr(turn_id),
+                                            _ptr(reward), eps_std, ddof, NORM[norm], _ptr(out["group_id"]),
+                                            _ptr(out["n_groups"]), _ptr(out["seg_offsets"]), _ptr(out["perm"]),
+                                            _ptr(out["adv"]), _ptr(out.get("group_mean")), _ptr(out.get("group_std")),
+                                            _ptr(out.get("data_error")), _stream())
+    _check(st, "at_grpo_group_advantage_static")
     return out
 
 

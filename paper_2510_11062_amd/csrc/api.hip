@@ -334,6 +334,7 @@ extern "C" const char* at_grpo_status_string(int32_t status) {
     case AT_GRPO_EUNSUPPORTED: return "unsupported dtype or shape";
     case AT_GRPO_EWORKSPACE: return "workspace missing, misaligned or too small";
     case AT_GRPO_EHIP: return "HIP runtime error";
+    case AT_GRPO_ESCRATCH: return "input exceeds the library's fixed scratch array (use the call that takes a workspace)";
     default: return "unknown status";
   }
 }

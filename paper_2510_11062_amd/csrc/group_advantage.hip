@@ -11,6 +11,8 @@
 // Three launch shapes, same device functions: everything in one workgroup (small batches: one
 // launch), five launches with a one-workgroup scan (key boxes up to 65536), seven launches with a
 // three-kernel scan (anything larger).
+#include <mutex>
+
 #include "common.hpp"
 
 namespace atg {
@@ -729,3 +731,64 @@ extern "C" int at_grpo_group_advantage_mixed(int32_t n_resp, int32_t n_env, int3
                              r_loc, alpha, reward, best, workspace, workspace_bytes, hip_stream);
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// The same call for callers that cannot allocate or hand over device scratch: the workspace is a
+// fixed array in device memory that belongs to the library.  Every GPU the library runs on holds
+// its own copy of the array (at its own address) until the process ends.
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+constexpr size_t kStaticScratchBytes = size_t{2} << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (looked up once per device; the array's name
+// is only a host-side handle and must never be passed to a kernel or a memory call).
+int static_scratch(void** out) {
+  int dev = -1;
+  ATG_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return AT_GRPO_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    ATG_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 255)) return AT_GRPO_EHIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return AT_GRPO_OK;
+}
+
+__global__ void k_ga_copy_error(const int32_t* __restrict__ err, int32_t* __restrict__ out) { *out = *err; }
+
+}  // namespace
+
+extern "C" size_t at_grpo_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" int at_grpo_group_advantage_static(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn,
+                                              const int32_t* env_id, const int32_t* agent_id,
+                                              const int32_t* turn_id, const float* reward, float eps_std,
+                                              int32_t ddof, int32_t norm, int32_t* group_id,
+                                              int32_t* n_groups, int32_t* seg_offsets, int32_t* perm,
+                                              float* adv, float* group_mean, float* group_std,
+                                              int32_t* data_error, void* hip_stream) {
+  if (!reward) return AT_GRPO_EINVAL;
+  if (n_resp <= 0 || n_env <= 0 || n_agent <= 0 || n_turn <= 0) return AT_GRPO_EINVAL;
+  const size_t need = group_advantage_workspace(n_resp, n_env, n_agent, n_turn);
+  if (need == 0 || need > kStaticScratchBytes) return AT_GRPO_ESCRATCH;
+  void* ws = nullptr;
+  ATG_TRY(static_scratch(&ws));
+  ATG_TRY(run_group_advantage(n_resp, n_env, n_agent, n_turn, env_id, agent_id, turn_id, reward, eps_std, ddof,
+                              norm, group_id, n_groups, seg_offsets, perm, adv, group_mean, group_std, nullptr,
+                              nullptr, 0.f, nullptr, nullptr, ws, kStaticScratchBytes, hip_stream));
+  if (data_error) {
+    hipLaunchKernelGGL(k_ga_copy_error, dim3(1), dim3(1), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const int32_t*>(ws), data_error);
+    ATG_LAUNCH_CHECK();
+  }
+  return AT_GRPO_OK;
+}
