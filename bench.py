@@ -44,17 +44,18 @@ def kernel_source_digest():
 
 
 def recorded_traffic(workload_name, kern):
-    """HBM bytes per working launch of `kern` from the committed rocprofv3 --pmc summary, or None when
-    there is none for this workload/kernel or the kernels changed since it was taken."""
+    """HBM bytes per working launch of `kern` from the committed rocprofv3 --pmc summary.  None when there
+    is no summary for this workload/kernel; the string "stale: ..." when the head kernel sources changed
+    since the counters were taken (they are then not quoted)."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload_name}.txt")
     if not os.path.exists(path):
         return None
     rec = json.load(open(path))
-    if rec.get("source_digest") != kernel_source_digest():
-        return None
+    now = kernel_source_digest()
+    if rec.get("source_digest") != now:
+        return f"stale: counters taken on sources {str(rec.get('source_digest'))[:12]}, now {now[:12]}"
     k = rec.get("kernels", {}).get(KERNEL_SYMBOL[kern])
     return None if k is None else k["hbm_bytes_per_launch"]
-
 
 
 def cpu_baseline(cfg, st, batch, old_logp, n_sample):
@@ -94,12 +95,104 @@ def cpu_baseline(cfg, st, batch, old_logp, n_sample):
             "extrapolated_full_workload_s": n_all / (n / dt)}
 
 
+def run_config(cfg, dev, steps, warmup):
+    """Times `steps` steps (grouped advantages + loss forward + backward) of one workload; returns the
+    measurements and what the caller needs for the CPU leg."""
+    wl = workload.build(cfg, dev)
+    st, batch, old_logp, resp_of_tok, valid = wl.st, wl.batch, wl.old_logp, wl.resp_of_tok, wl.valid
+    env_id, agent_id, turn_id, reward = wl.env_id, wl.agent_id, wl.turn_id, wl.reward
+    eps = cfg.eps_clip
+    d_hidden = torch.empty_like(batch.hidden)
+    dW = [torch.empty(w.shape, dtype=torch.float32, device=dev) for w in batch.W]
+    state = {}
+
+    def step():
+        ga = api.at_grpo_group_advantage(env_id, agent_id, turn_id, reward, cfg.E, cfg.N, cfg.T, want_stats=False)
+        fwd = api.at_grpo_policy_loss_fwd(batch, old_logp, ga["adv"], eps, eps, out=state.get("fwd"))
+        api.at_grpo_policy_loss_bwd(batch, old_logp, ga["adv"], fwd["logp"], fwd["lse"], eps, eps,
+                                    dW=dW, d_hidden=d_hidden)
+        state["fwd"], state["ga"] = fwd, ga
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    api.at_grpo_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = api.at_grpo_profile_read()
+    api.at_grpo_profile_enable(False)
+
+    n_valid = int(valid.sum().item())
+    fwd, ga = state["fwd"], state["ga"]
+    err = api.error_word(fwd["workspace"])
+    # rows that carry gradient: participating, advantage != 0, not on the clipped branch
+    A_tok = ga["adv"][resp_of_tok]
+    grad_rows = valid & (A_tok != 0) & ((fwd["clip_mask"] & 4) == 0)
+    n_grad = int(grad_rows.sum().item())
+    hv2 = 2.0 * cfg.H * cfg.V
+    flops = {"head_fwd": hv2 * n_valid, "head_dz": hv2 * n_grad, "head_dh": hv2 * n_grad, "head_dw": hv2 * n_grad}
+    kern = max(flops, key=lambda k: prof[k][1])
+    kern_ms = prof[kern][1] / steps
+    achieved = flops[kern] / (kern_ms * 1e-3) / 1e12
+    # launches that had rows to process (the others return at once): per head, ceil(rows / chunk)
+    live = valid if kern == "head_fwd" else grad_rows
+    rows_per_head = torch.bincount(wl.head_of_tok[live], minlength=cfg.n_heads).tolist()
+    work_launches = sum(-(-r // CHUNK_TOKENS) for r in rows_per_head)
+    peak = PEAK[cfg.dtype]
+    all_gemm_ms = sum(prof[k][1] for k in flops) / steps
+    all_gemm_tflops = sum(flops.values()) / (all_gemm_ms * 1e-3) / 1e12
+    rec = {
+        "workload": f"{cfg.name}: H={cfg.H} V={cfg.V} heads={cfg.n_heads} "
+                    f"E{cfg.E}xN{cfg.N}xT{cfg.T}xK{cfg.K}={st.cfg.n_resp} responses, "
+                    f"{n_valid} response tokens in {st.n_tok} rows"
+                    f"{' (padded + mask)' if cfg.padded else ' (packed)'}",
+        "tokens_per_s": n_valid / (elapsed / steps), "ms_per_step": elapsed / steps * 1e3, "steps": steps,
+        "response_tokens": n_valid, "rows_with_gradient": n_grad, "device_error_word": err,
+        "roofline": {"bound": "mfma", "kernel": kern, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": recorded_traffic(cfg.name, kern),
+                     "flop_per_launch": flops[kern] / max(work_launches, 1),
+                     "ms_per_launch": kern_ms / max(work_launches, 1),
+                     "launches_with_rows_per_step": work_launches,
+                     "kernel_ms_per_step": kern_ms, "launches_per_step": prof[kern][0] / steps,
+                     "all_head_contractions_tflops": all_gemm_tflops,
+                     "all_head_contractions_frac": all_gemm_tflops / peak},
+        "head_kernel_tflops": {k: flops[k] / (prof[k][1] / steps * 1e-3) / 1e12 for k in flops},
+        "kernel_ms_per_step": {k: v[1] / steps for k, v in prof.items()},
+    }
+    return rec, (st, batch, old_logp)
+
+
+def streaming_records(dev):
+    """Achieved HBM GB/s of the grouping call, the surrogate stage and the head update (the bandwidth half
+    of the metric), measured in this run: the grouping call and the surrogate stage at the largest real
+    shapes (latency-bound there) and on scaled twins, the update on the C2 head."""
+    from paper_2510_11062_amd import bench_streaming as bs
+    out = [bs.grouping(dev, 256, 2, 10, 4, "C4 shape (20480 responses)"),
+           bs.grouping(dev, 262144, 2, 4, 8, "scaled twin of C2: 2^24 responses, K = 8, shuffled order"),
+           bs.grouping(dev, 262144, 2, 4, 8, "scaled twin of C2: 2^24 responses, K = 8, rollout order", shuffle=False),
+           bs.surrogate(dev, 6144, 290, "C5 row count (~1.8 M rows)"),
+           bs.surrogate(dev, 6144 * 16, 290, "16x twin of C5 (~28 M rows)"),
+           bs.head_update(dev, 1, 151936, 2048, "C2 head: V=151936 H=2048, bf16 weights + fp32 master")]
+    copy = bs.copy_ceiling(dev)
+    for o in out:
+        o["frac_of_measured_copy"] = o["achieved"] / copy["achieved"]
+    return {"hbm_peak_GBs": bs.HBM_PEAK_GBS, "measured_copy_ceiling": copy, "kernels": out}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", default="C2")
+    ap.add_argument("--config", default="C2", help="the workload `value` is quoted on")
+    ap.add_argument("--more-configs", default="C3,C4,C5",
+                    help="further workloads timed after it and reported under `configs` ('none' to skip)")
+    ap.add_argument("--more-steps", type=int, default=3, help="timed steps of each further workload")
+    ap.add_argument("--no-streaming", action="store_true", help="skip the bandwidth records of the streaming kernels")
     ap.add_argument("--cpu-sample", type=int, default=6144, help="response tokens given to the CPU oracle (0 = skip)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 1 GiB with torch (known traffic, to scale HBM counters)")
@@ -115,43 +208,7 @@ def main():
     cfg = synth.CONFIGS[args.config]
     api.load_library()
 
-    wl = workload.build(cfg, dev)
-    st, batch, old_logp, resp_of_tok, valid = wl.st, wl.batch, wl.old_logp, wl.resp_of_tok, wl.valid
-    env_id, agent_id, turn_id, reward = wl.env_id, wl.agent_id, wl.turn_id, wl.reward
-    eps = cfg.eps_clip
-
-    d_hidden = torch.empty_like(batch.hidden)
-    dW = [torch.empty(w.shape, dtype=torch.float32, device=dev) for w in batch.W]
-    state = {}
-
-    def step():
-        ga = api.at_grpo_group_advantage(env_id, agent_id, turn_id, reward, cfg.E, cfg.N, cfg.T, want_stats=False)
-        fwd = api.at_grpo_policy_loss_fwd(batch, old_logp, ga["adv"], eps, eps, out=state.get("fwd"))
-        api.at_grpo_policy_loss_bwd(batch, old_logp, ga["adv"], fwd["logp"], fwd["lse"], eps, eps,
-                                    dW=dW, d_hidden=d_hidden)
-        state["fwd"], state["ga"] = fwd, ga
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    api.at_grpo_profile_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    prof = api.at_grpo_profile_read()
-    api.at_grpo_profile_enable(False)
-
-    n_valid = int(valid.sum().item())
-    fwd, ga = state["fwd"], state["ga"]
-    err = api.error_word(fwd["workspace"])
-    # rows that carry gradient: participating, advantage != 0, not on the clipped branch
-    A_tok = ga["adv"][resp_of_tok]
-    n_grad = int((valid & (A_tok != 0) & ((fwd["clip_mask"] & 4) == 0)).sum().item())
-    ms_per_step = elapsed / args.steps * 1e3
-    tokens_per_s = n_valid / (elapsed / args.steps)
+    rec, (st, batch, old_logp) = run_config(cfg, dev, args.steps, args.warmup)
 
     if args.calibration_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -160,42 +217,34 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    hv2 = 2.0 * cfg.H * cfg.V
-    flops = {"head_fwd": hv2 * n_valid, "head_dz": hv2 * n_grad, "head_dh": hv2 * n_grad, "head_dw": hv2 * n_grad}
-    kern = max(flops, key=lambda k: prof[k][1])
-    kern_ms = prof[kern][1] / args.steps
-    achieved = flops[kern] / (kern_ms * 1e-3) / 1e12
-    # launches that had rows to process (the others return at once): per head, ceil(rows / chunk)
-    head_of_tok = wl.head_of_tok
-    live = valid if kern == "head_fwd" else (valid & (A_tok != 0) & ((fwd["clip_mask"] & 4) == 0))
-    rows_per_head = torch.bincount(head_of_tok[live], minlength=cfg.n_heads).tolist()
-    work_launches = sum(-(-r // CHUNK_TOKENS) for r in rows_per_head)
-    peak = PEAK[cfg.dtype]
-    all_gemm_ms = sum(prof[k][1] for k in flops) / args.steps
-    all_gemm_tflops = sum(flops.values()) / (all_gemm_ms * 1e-3) / 1e12
-
     out = {
         "metric": "policy-loss fwd+bwd tokens/sec at V=151936; MFMA util % and HBM GB/s",
-        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": rec["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": rec["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: H={cfg.H} V={cfg.V} heads={cfg.n_heads} "
-                               f"E{cfg.E}xN{cfg.N}xT{cfg.T}xK{cfg.K}={st.cfg.n_resp} responses, "
-                               f"{n_valid} response tokens in {st.n_tok} rows"
-                               f"{' (padded + mask)' if cfg.padded else ' (packed)'}",
-                   "rows_with_gradient": n_grad, "device_error_word": err},
-        "roofline": {"bound": "mfma", "kernel": kern, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": recorded_traffic(cfg.name, kern),
-                     "flop_per_launch": flops[kern] / max(work_launches, 1),
-                     "ms_per_launch": kern_ms / max(work_launches, 1),
-                     "launches_with_rows_per_step": work_launches,
-                     "kernel_ms_per_step": kern_ms, "launches_per_step": prof[kern][0] / args.steps,
-                     "all_head_contractions_tflops": all_gemm_tflops,
-                     "all_head_contractions_frac": all_gemm_tflops / peak},
-        "kernel_ms_per_step": {k: v[1] / args.steps for k, v in prof.items()},
+        "config": {"workload": rec["workload"], "rows_with_gradient": rec["rows_with_gradient"],
+                   "device_error_word": rec["device_error_word"]},
+        "roofline": rec["roofline"],
+        "head_kernel_tflops": rec["head_kernel_tflops"],
+        "kernel_ms_per_step": rec["kernel_ms_per_step"],
     }
     if args.cpu_sample > 0:
         out["cpu_baseline"] = cpu_baseline(cfg, st, batch, old_logp, args.cpu_sample)
+    del st, batch, old_logp
+    api.release_workspace()
+    torch.cuda.empty_cache()
+
+    if args.more_configs.lower() != "none":
+        out["configs"] = {}
+        for name in [c for c in args.more_configs.split(",") if c and c != args.config]:
+            more, keep = run_config(synth.CONFIGS[name], dev, args.more_steps, 1)
+            more.pop("kernel_ms_per_step")
+            out["configs"][name] = more
+            del keep
+            api.release_workspace()
+            torch.cuda.empty_cache()
+    if not args.no_streaming:
+        out["streaming"] = streaming_records(dev)
     print(json.dumps(out))
 
 

@@ -51,10 +51,19 @@ typedef enum { AT_GRPO_AGG_TOKEN_MEAN = 0, AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN = 1 }
 /* F_norm of Eq. (1): the group's standard deviation (plus eps_std), or 1. */
 typedef enum { AT_GRPO_NORM_STD = 0, AT_GRPO_NORM_NONE = 1 } at_grpo_norm;
 
+/* Which responses form a group in Eq. (1): the paper's agent- and turn-wise key, or one of the two
+ * groupings it argues against (Sec. 4.1, Fig. 3; Sec. 5.3), kept for comparison runs. */
+typedef enum {
+  AT_GRPO_GROUP_BY_AGENT_TURN = 0, /* (e, i, t): AT-GRPO, Alg. 1                                      */
+  AT_GRPO_GROUP_BY_TRAJECTORY = 1, /* e alone: every candidate of a task in one group (GRPO on the MAS) */
+  AT_GRPO_GROUP_BY_PARALLEL = 2    /* (e, i, t) at t = 0, one group per candidate at t > 0: what
+                                      sampling K whole trajectories in parallel yields               */
+} at_grpo_group_by;
+
 /* Bits of the device error word (workspace[0]). */
 enum {
   AT_GRPO_DATA_ID_RANGE = 1,     /* env/agent/turn id outside its extent              */
-  AT_GRPO_DATA_REWARD = 2,       /* non-finite reward                                 */
+  AT_GRPO_DATA_REWARD = 2,       /* non-finite reward (the response then takes no part) */
   AT_GRPO_DATA_TOKEN_RANGE = 4,  /* token_id outside [0, V) on an unmasked row        */
   AT_GRPO_DATA_SEQLENS = 8,      /* cu_seqlens not monotone within [0, n_tok]         */
   AT_GRPO_DATA_AGENT_RANGE = 16  /* resp_agent / head_of_agent entry out of range     */
@@ -110,7 +119,9 @@ typedef struct {
  *
  * key(r) = (env_id[r] * n_agent + agent_id[r]) * n_turn + turn_id[r]; groups are numbered
  * densely in ascending key order; keys that do not occur produce no group.
- *   group_id[R]      dense group of each response (-1 for a response with an id out of range)
+ *   group_id[R]      dense group of each response (-1 for a response with an id out of range or a
+ *                    non-finite reward: it joins no group, gets advantage 0 and does not touch the
+ *                    statistics of the others)
  *   n_groups[1]      G
  *   seg_offsets[G+1] CSR offsets into perm; the buffer must hold min(R, n_env*n_agent*n_turn)+1
  *   perm[R]          responses sorted by key, ties in ascending original index (stable)
@@ -118,8 +129,10 @@ typedef struct {
  *                    [NORM_NONE]; std uses divisor n_g - ddof (0 if that is <= 0); a group
  *                    whose rewards are all the same fp32 value gets exactly 0
  *   group_mean[G], group_std[G]  optional (NULL to skip)
- * ddof is 0 or 1.  Arithmetic is fp32, sequential in perm order inside a group, hence
- * deterministic.
+ * ddof is 0 or 1.  Arithmetic is fp32, two passes (mean, then squared deviations): groups of up to 16
+ * members are summed sequentially in perm order, larger ones as 64 lane-strided partial sums (member
+ * j of the group goes to partial j mod 64) that are combined in a fixed order; either way the result
+ * does not depend on the order in which the responses arrive or on the run.
  */
 int at_grpo_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn,
                             const int32_t* env_id, const int32_t* agent_id, const int32_t* turn_id,
@@ -127,6 +140,26 @@ int at_grpo_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int3
                             int32_t* group_id, int32_t* n_groups, int32_t* seg_offsets,
                             int32_t* perm, float* adv, float* group_mean, float* group_std,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * at_grpo_group_advantage under another grouping key (`group_by`, see at_grpo_group_by): everything
+ * else, including the canonical numbering (ascending key), is the same.
+ *   TRAJECTORY  key = e: agent_id and turn_id are only range-checked; seg_offsets needs min(R, n_env) + 1
+ *   PARALLEL    key = ((e * n_agent + i) * n_turn + t) * n_sample + (t > 0 ? sample_id[r] : 0), with
+ *               sample_id[R] the candidate index c in [0, n_sample): every group at t > 0 is a single
+ *               response and gets advantage 0 (the degenerate case Sec. 4.1 describes);
+ *               seg_offsets needs min(R, n_env * n_agent * n_turn * n_sample) + 1 entries
+ * sample_id and n_sample are ignored otherwise.  Workspace: at_grpo_group_advantage_keyed_workspace_bytes.
+ */
+int at_grpo_group_advantage_keyed(int32_t group_by, int32_t n_resp, int32_t n_env, int32_t n_agent,
+                                  int32_t n_turn, int32_t n_sample, const int32_t* env_id,
+                                  const int32_t* agent_id, const int32_t* turn_id, const int32_t* sample_id,
+                                  const float* reward, float eps_std, int32_t ddof, int32_t norm,
+                                  int32_t* group_id, int32_t* n_groups, int32_t* seg_offsets, int32_t* perm,
+                                  float* adv, float* group_mean, float* group_std, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream);
+size_t at_grpo_group_advantage_keyed_workspace_bytes(int32_t group_by, int32_t n_resp, int32_t n_env,
+                                                     int32_t n_agent, int32_t n_turn, int32_t n_sample);
 
 /*
  * The same with the step in front of it: agent-wise credit assignment, Eq. (3) of Sec. 4.1,

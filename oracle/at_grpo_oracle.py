@@ -14,6 +14,9 @@ fp64 here and are never re-rounded.
 Paper passages followed (arXiv 2510.11062):
   * group key  g = hash(e, i, t)                      -- Alg. 1 (Phase 1), Sec. 4.1
                                                         "Agent- and Turn-wise Grouping"
+  * the groupings it is compared with                  -- Sec. 4.1 / Fig. 3 (parallel sampling:
+                                                        groups of one after the first turn),
+                                                        Sec. 5.3 (trajectory-level groups)
   * group-relative advantage                           -- Sec. 3 "Group-based RL", Eq. (1)
   * per-model batch B_m and clipped surrogate          -- Sec. 3, Eq. (2)
   * response-token credit (reward mask)                -- Sec. 4.1, first paragraph
@@ -57,6 +60,31 @@ def group_key(env_id, agent_id, turn_id, n_agent: int, n_turn: int) -> np.ndarra
     i = np.asarray(agent_id, dtype=np.int64)
     t = np.asarray(turn_id, dtype=np.int64)
     return (e * int(n_agent) + i) * int(n_turn) + t
+
+
+def group_key_by(env_id, agent_id, turn_id, sample_id, n_agent: int, n_turn: int, n_sample: int,
+                 group_by: str = "agent_turn") -> np.ndarray:
+    """Keys of the groupings the paper sets its own against.
+
+    "agent_turn"  (e, i, t): AT-GRPO (Alg. 1), the same key as group_key.
+    "trajectory"  e alone: every candidate of a task in one group, whichever agent and turn produced
+                  it (GRPO applied to the multi-agent system as a whole, Sec. 5.3).
+    "parallel"    K trajectories sampled in parallel from the task's start (Sec. 4.1, Fig. 3): the
+                  candidates share a state only at the first turn, so the key is (e, i, 0) at t = 0 and
+                  (e, i, t, c) with the candidate index c afterwards: groups of one.
+    Keys are packed so that ascending key is the lexicographic order of the tuple.
+    """
+    e = np.asarray(env_id, dtype=np.int64)
+    i = np.asarray(agent_id, dtype=np.int64)
+    t = np.asarray(turn_id, dtype=np.int64)
+    if group_by == "agent_turn":
+        return (e * int(n_agent) + i) * int(n_turn) + t
+    if group_by == "trajectory":
+        return e.copy()
+    if group_by == "parallel":
+        c = np.asarray(sample_id, dtype=np.int64)
+        return ((e * int(n_agent) + i) * int(n_turn) + t) * int(n_sample) + np.where(t > 0, c, 0)
+    raise ValueError(group_by)
 
 
 def group_segments(key: np.ndarray):

@@ -19,12 +19,14 @@ _lib = None
 
 AGG = {"token_mean": 0, "seq_mean_token_mean": 1}
 NORM = {"std": 0, "none": 1}
+GROUP_BY = {"agent_turn": 0, "trajectory": 1, "parallel": 2}
 CALL_GROUP_ADVANTAGE, CALL_TOKEN_LOGPROB, CALL_POLICY_LOSS_FWD, CALL_POLICY_LOSS_BWD, CALL_SURROGATE, \
     CALL_HEAD_UPDATE, CALL_DIAGNOSTICS, CALL_TOKEN_ENTROPY = range(8)
 DTYPE = {torch.float32: 0, torch.bfloat16: 1}
 
 EXPORTS = [
     "at_grpo_group_advantage", "at_grpo_group_advantage_mixed", "at_grpo_group_advantage_static",
+    "at_grpo_group_advantage_keyed", "at_grpo_group_advantage_keyed_workspace_bytes",
     "at_grpo_static_scratch_bytes", "at_grpo_token_logprob", "at_grpo_surrogate_from_logp",
     "at_grpo_surrogate_diagnostics", "at_grpo_token_entropy",
     "at_grpo_policy_loss_fwd", "at_grpo_policy_loss_bwd", "at_grpo_head_update", "at_grpo_workspace_bytes",
@@ -73,6 +75,11 @@ def load_library():
     lib.at_grpo_group_advantage_mixed.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, f32, f32, i32, i32,
                                                   vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.at_grpo_group_advantage_mixed.restype = C.c_int
+    lib.at_grpo_group_advantage_keyed.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, f32, i32, i32,
+                                                  vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.at_grpo_group_advantage_keyed.restype = C.c_int
+    lib.at_grpo_group_advantage_keyed_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
+    lib.at_grpo_group_advantage_keyed_workspace_bytes.restype = sz
     lib.at_grpo_group_advantage_static.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, f32, i32, i32,
                                                    vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.at_grpo_group_advantage_static.restype = C.c_int
@@ -131,22 +138,41 @@ def _dev_check(*tensors):
 
 
 _workspace_cache = {}
+_workspace_retired = []
 
 
 def _workspace(nbytes: int, device) -> torch.Tensor:
-    """A cached scratch tensor (one per device), grown on demand."""
-    key = str(device)
+    """A cached scratch tensor per (device, stream), grown on demand.
+
+    Calls on different streams never share scratch (nothing orders them).  A workspace that is outgrown
+    is kept alive until release_workspace(): a HIP graph captured earlier holds its raw pointer, and a
+    replay must not find that memory handed to somebody else."""
+    key = (str(device), int(torch.cuda.current_stream(device).cuda_stream))
     ws = _workspace_cache.get(key)
     if ws is None or ws.numel() < nbytes:
-        _workspace_cache.pop(key, None)
-        ws = None
+        if ws is not None:
+            _workspace_retired.append(ws)
         ws = torch.empty(int(nbytes), dtype=torch.uint8, device=device)
         _workspace_cache[key] = ws
     return ws
 
 
 def release_workspace():
+    """Drops every cached workspace (only when no captured graph that used the binding will be replayed)."""
     _workspace_cache.clear()
+    _workspace_retired.clear()
+
+
+def _i32_check(**tensors):
+    for name, t in tensors.items():
+        if t is not None and t.dtype != torch.int32:
+            raise AtGrpoError(f"{name} must be int32, got {t.dtype}")
+
+
+def _f32_check(**tensors):
+    for name, t in tensors.items():
+        if t is not None and t.dtype != torch.float32:
+            raise AtGrpoError(f"{name} must be float32, got {t.dtype}")
 
 
 @dataclass
@@ -215,6 +241,8 @@ def at_grpo_group_advantage(env_id, agent_id, turn_id, reward, n_env: int, n_age
     """Returns dict(group_id, n_groups, seg_offsets, perm, adv, group_mean, group_std, workspace)."""
     lib = load_library()
     _dev_check(env_id, agent_id, turn_id, reward)
+    _f32_check(reward=reward)
+    _i32_check(env_id=env_id, agent_id=agent_id, turn_id=turn_id)
     dev = reward.device
     R = reward.numel()
     n_keys = n_env * n_agent * n_turn
@@ -257,6 +285,32 @@ def group_advantage_outputs(R: int, n_keys: int, dev, want_stats: bool = True):
     )
 
 
+def at_grpo_group_advantage_keyed(group_by: str, env_id, agent_id, turn_id, reward, n_env: int, n_agent: int,
+                                  n_turn: int, sample_id=None, n_sample: int = 1, eps_std: float = 1e-6,
+                                  ddof: int = 0, norm: str = "std"):
+    """at_grpo_group_advantage under the grouping `group_by` ("agent_turn", "trajectory", "parallel")."""
+    lib = load_library()
+    _dev_check(env_id, agent_id, turn_id, reward, sample_id)
+    _f32_check(reward=reward)
+    _i32_check(env_id=env_id, agent_id=agent_id, turn_id=turn_id, sample_id=sample_id)
+    R = reward.numel()
+    mode = GROUP_BY[group_by]
+    n_keys = n_env if mode == 1 else n_env * n_agent * n_turn * (n_sample if mode == 2 else 1)
+    out = group_advantage_outputs(R, n_keys, reward.device)
+    nbytes = lib.at_grpo_group_advantage_keyed_workspace_bytes(mode, R, n_env, n_agent, n_turn, n_sample)
+    if nbytes == 0:
+        raise AtGrpoError("at_grpo_group_advantage_keyed_workspace_bytes rejected the extents")
+    ws = _workspace(nbytes, reward.device)
+    st = lib.at_grpo_group_advantage_keyed(mode, R, n_env, n_agent, n_turn, n_sample, _ptr(env_id), _ptr(agent_id),
+                                           _ptr(turn_id), _ptr(sample_id), _ptr(reward), eps_std, ddof, NORM[norm],
+                                           _ptr(out["group_id"]), _ptr(out["n_groups"]), _ptr(out["seg_offsets"]),
+                                           _ptr(out["perm"]), _ptr(out["adv"]), _ptr(out["group_mean"]),
+                                           _ptr(out["group_std"]), _ptr(ws), ws.numel(), _stream())
+    _check(st, "at_grpo_group_advantage_keyed")
+    out["workspace"] = ws
+    return out
+
+
 def at_grpo_static_scratch_bytes() -> int:
     return int(load_library().at_grpo_static_scratch_bytes())
 
@@ -269,6 +323,8 @@ def at_grpo_group_advantage_static(env_id, agent_id, turn_id, reward, n_env: int
     either).  Returns the dict of outputs, data_error[1] holding the call's error word."""
     lib = load_library()
     _dev_check(env_id, agent_id, turn_id, reward)
+    _f32_check(reward=reward)
+    _i32_check(env_id=env_id, agent_id=agent_id, turn_id=turn_id)
     R = reward.numel()
     if out is None:
         out = group_advantage_outputs(R, n_env * n_agent * n_turn, reward.device)
@@ -289,6 +345,8 @@ def at_grpo_group_advantage_mixed(env_id, agent_id, turn_id, r_team, r_loc, alph
     Returns the dict of at_grpo_group_advantage extended by reward[R] and best[min(R, keys)]."""
     lib = load_library()
     _dev_check(env_id, agent_id, turn_id, r_team, r_loc)
+    _f32_check(r_team=r_team, r_loc=r_loc)
+    _i32_check(env_id=env_id, agent_id=agent_id, turn_id=turn_id)
     dev = r_team.device
     R = r_team.numel()
     n_keys = n_env * n_agent * n_turn
@@ -377,6 +435,7 @@ def at_grpo_surrogate_from_logp(batch: Batch, logp, old_logp, adv, eps_low: floa
     lib = load_library()
     cb = batch.to_c()
     _dev_check(logp, old_logp, adv)
+    _f32_check(logp=logp, old_logp=old_logp, adv=adv)
     dev = logp.device
     loss = torch.empty(cb.n_heads, dtype=torch.float32, device=dev)
     clip_mask = torch.empty(cb.n_tok, dtype=torch.uint8, device=dev)
@@ -395,6 +454,7 @@ def at_grpo_surrogate_diagnostics(batch: Batch, logp, old_logp, adv, eps_low: fl
     lib = load_library()
     cb = batch.to_c()
     _dev_check(logp, old_logp, adv)
+    _f32_check(logp=logp, old_logp=old_logp, adv=adv)
     dev = logp.device
     counts = torch.empty((cb.n_heads, 4), dtype=torch.int32, device=dev)
     stats = torch.empty((cb.n_heads, 2), dtype=torch.float32, device=dev)
@@ -410,6 +470,7 @@ def at_grpo_policy_loss_fwd(batch: Batch, old_logp, adv, eps_low: float, eps_hig
     lib = load_library()
     cb = batch.to_c()
     _dev_check(old_logp, adv)
+    _f32_check(old_logp=old_logp, adv=adv)
     dev = batch.hidden.device
     if out is None:
         out = dict(
@@ -435,6 +496,9 @@ def at_grpo_policy_loss_bwd(batch: Batch, old_logp, adv, logp, lse, eps_low: flo
     lib = load_library()
     cb = batch.to_c()
     _dev_check(old_logp, adv, logp, lse, grad_loss, d_hidden)
+    _f32_check(old_logp=old_logp, adv=adv, logp=logp, lse=lse, grad_loss=grad_loss)
+    if d_hidden is not None and (d_hidden.dtype != batch.hidden.dtype or d_hidden.shape != batch.hidden.shape):
+        raise AtGrpoError("d_hidden must have hidden's dtype and shape")
     dev = batch.hidden.device
     if d_hidden is None:
         d_hidden = torch.empty_like(batch.hidden)

@@ -125,6 +125,16 @@ def head_update(dev, n_heads, V, H, label):
             "frac": 34.0 * n / dt / 1e9 / HBM_PEAK_GBS}
 
 
+def copy_ceiling(dev, n_bytes: int = 1 << 30):
+    """What a plain device-to-device copy of 1 GiB reaches on this GPU (bytes read + written per second):
+    the measured ceiling the streaming kernels are also reported against."""
+    src = torch.empty(n_bytes // 4, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    dt = _time(lambda: dst.copy_(src), iters=10)
+    return {"kernel": "torch device-to-device copy", "bytes": n_bytes, "us_per_call": dt * 1e6,
+            "achieved": 2.0 * n_bytes / dt / 1e9, "unit": "GB/s", "frac": 2.0 * n_bytes / dt / 1e9 / HBM_PEAK_GBS}
+
+
 def main():
     if not torch.cuda.is_available():
         print("needs a GPU", file=sys.stderr)
@@ -142,6 +152,7 @@ def main():
     out.append(surrogate(dev, 6144 * 16, 290, "16x twin of C5 (~28 M rows)"))
     out.append(head_update(dev, 1, 151936, 2048, "C2 head: V=151936 H=2048, bf16 weights + fp32 master"))
     out.append(head_update(dev, 2, 151936, 4096, "C3 heads: 2 x (V=151936 H=4096)"))
+    out.append(copy_ceiling(dev))
     for o in out:
         print(json.dumps(o))
 

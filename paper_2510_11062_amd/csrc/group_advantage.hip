@@ -28,13 +28,37 @@ struct GaArgs {
   const int32_t* agent_id;
   const int32_t* turn_id;
   const float* reward;
+  int32_t group_by;          // at_grpo_group_by
+  int32_t n_sample;          // extent of sample_id (AT_GRPO_GROUP_BY_PARALLEL only)
+  const int32_t* sample_id;  // candidate index c of each response (AT_GRPO_GROUP_BY_PARALLEL only)
 };
 
+// Key of a response under the chosen grouping (ascending key = canonical group order):
+//   AGENT_TURN  (e, i, t)                         the paper's grouping (Alg. 1, Sec. 4.1)
+//   TRAJECTORY  e                                 all candidates of a task in one group, whatever agent
+//                                                 and turn produced them (GRPO applied to the whole MAS)
+//   PARALLEL    (e, i, t, c if t > 0 else 0)      K trajectories sampled in parallel share a state only at
+//                                                 the first turn; later turns are groups of one (Sec. 4.1)
+// A response with an id outside its extent has no key.
 __device__ __forceinline__ int64_t key_of(const GaArgs& a, int r, bool* ok) {
   const int e = a.env_id[r], i = a.agent_id[r], t = a.turn_id[r];
-  *ok = e >= 0 && e < a.n_env && i >= 0 && i < a.n_agent && t >= 0 && t < a.n_turn;
-  return (static_cast<int64_t>(e) * a.n_agent + i) * a.n_turn + t;
+  bool in = e >= 0 && e < a.n_env && i >= 0 && i < a.n_agent && t >= 0 && t < a.n_turn;
+  int64_t key;
+  if (a.group_by == AT_GRPO_GROUP_BY_TRAJECTORY) {
+    key = e;
+  } else {
+    key = (static_cast<int64_t>(e) * a.n_agent + i) * a.n_turn + t;
+    if (a.group_by == AT_GRPO_GROUP_BY_PARALLEL) {
+      const int c = a.sample_id[r];
+      in = in && c >= 0 && c < a.n_sample;
+      key = key * a.n_sample + (t > 0 ? c : 0);
+    }
+  }
+  *ok = in;
+  return key;
 }
+
+__device__ __forceinline__ bool finite_reward(float x) { return fabsf(x) <= 3.402823466e38f; }
 
 // Histogram over the key box.  The atomic's return value is the response's arrival rank inside its
 // group.  Neighbouring lanes with the same key (candidates of one group emitted together, the
@@ -48,12 +72,12 @@ __global__ __launch_bounds__(256) void k_ga_hist(GaArgs a, int32_t* __restrict__
   if (r < a.n_resp) {
     bool ok;
     const int64_t k64 = key_of(a, r, &ok);
-    if (ok) {
-      key = static_cast<int32_t>(k64);
-      const float x = a.reward[r];
-      if (!(fabsf(x) <= 3.402823466e38f)) atomicOr(err, AT_GRPO_DATA_REWARD);
-    } else {
+    if (!ok) {
       atomicOr(err, AT_GRPO_DATA_ID_RANGE);
+    } else if (!finite_reward(a.reward[r])) {
+      atomicOr(err, AT_GRPO_DATA_REWARD);     // takes no part: no group, advantage 0
+    } else {
+      key = static_cast<int32_t>(k64);
     }
     key_of_resp[r] = key;
   }
@@ -443,13 +467,13 @@ __global__ __launch_bounds__(kSingleThreads) void k_ga_single(
     bool ok;
     const int64_t k64 = key_of(a, r, &ok);
     int key = -1;
-    if (ok) {
-      key = static_cast<int>(k64);
-      const float x = a.reward[r];
-      if (!(fabsf(x) <= 3.402823466e38f)) atomicOr(err, AT_GRPO_DATA_REWARD);
-      rank_of_resp[r] = atomicAdd(&hist[key], 1);
-    } else {
+    if (!ok) {
       atomicOr(err, AT_GRPO_DATA_ID_RANGE);
+    } else if (!finite_reward(a.reward[r])) {
+      atomicOr(err, AT_GRPO_DATA_REWARD);     // takes no part: no group, advantage 0
+    } else {
+      key = static_cast<int>(k64);
+      rank_of_resp[r] = atomicAdd(&hist[key], 1);
     }
     key_of_resp[r] = key;
   }
@@ -589,10 +613,18 @@ struct GaPlan {
   int32_t *err, *hist, *gid_of_key, *key_of_resp, *rank_of_resp, *arrival, *bsum_p, *bsum_c;
 };
 
-bool plan(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn, WsAlloc& ws, GaPlan* p) {
+int64_t key_box(int32_t n_env, int32_t n_agent, int32_t n_turn, int32_t group_by, int32_t n_sample) {
+  if (group_by == AT_GRPO_GROUP_BY_TRAJECTORY) return n_env;
+  const int64_t eit = static_cast<int64_t>(n_env) * n_agent * n_turn;
+  if (group_by == AT_GRPO_GROUP_BY_PARALLEL) return n_sample > 0 && eit <= (int64_t{1} << 28) ? eit * n_sample : -1;
+  return eit;
+}
+
+bool plan(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn, int32_t group_by, int32_t n_sample,
+          WsAlloc& ws, GaPlan* p) {
   if (n_resp <= 0 || n_env <= 0 || n_agent <= 0 || n_turn <= 0) return false;
-  const int64_t n_keys = static_cast<int64_t>(n_env) * n_agent * n_turn;
-  if (n_keys > (int64_t{1} << 28)) return false;
+  const int64_t n_keys = key_box(n_env, n_agent, n_turn, group_by, n_sample);
+  if (n_keys <= 0 || n_keys > (int64_t{1} << 28)) return false;
   p->n_keys = n_keys;
   p->n_blocks = ceil_div(n_keys, kKeysPerBlock);
   p->err = ws.take<int32_t>(64);
@@ -608,11 +640,16 @@ bool plan(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn, WsAllo
 
 }  // namespace
 
-size_t group_advantage_workspace(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn) {
+size_t group_advantage_workspace(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn, int32_t group_by,
+                                 int32_t n_sample) {
   WsAlloc ws(nullptr);
   GaPlan p;
-  if (!plan(n_resp, n_env, n_agent, n_turn, ws, &p)) return 0;
+  if (!plan(n_resp, n_env, n_agent, n_turn, group_by, n_sample, ws, &p)) return 0;
   return ws.bytes();
+}
+
+size_t group_advantage_workspace(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t n_turn) {
+  return group_advantage_workspace(n_resp, n_env, n_agent, n_turn, AT_GRPO_GROUP_BY_AGENT_TURN, 1);
 }
 
 }  // namespace atg
@@ -627,16 +664,22 @@ int run_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t 
                         int32_t* n_groups, int32_t* seg_offsets, int32_t* perm, float* adv,
                         float* group_mean, float* group_std, const float* r_team, const float* r_loc,
                         float alpha, float* reward_out, int32_t* best, void* workspace,
-                        size_t workspace_bytes, void* hip_stream) {
+                        size_t workspace_bytes, void* hip_stream,
+                        int32_t group_by = AT_GRPO_GROUP_BY_AGENT_TURN, const int32_t* sample_id = nullptr,
+                        int32_t n_sample = 1) {
   if (!env_id || !agent_id || !turn_id || !group_id || !n_groups || !seg_offsets || !perm || !adv)
     return AT_GRPO_EINVAL;
   if (n_resp <= 0 || n_env <= 0 || n_agent <= 0 || n_turn <= 0) return AT_GRPO_EINVAL;
+  if (group_by != AT_GRPO_GROUP_BY_AGENT_TURN && group_by != AT_GRPO_GROUP_BY_TRAJECTORY &&
+      group_by != AT_GRPO_GROUP_BY_PARALLEL)
+    return AT_GRPO_EINVAL;
+  if (group_by == AT_GRPO_GROUP_BY_PARALLEL && (!sample_id || n_sample <= 0)) return AT_GRPO_EINVAL;
   if (ddof != 0 && ddof != 1) return AT_GRPO_EINVAL;
   if (norm != AT_GRPO_NORM_STD && norm != AT_GRPO_NORM_NONE) return AT_GRPO_EINVAL;
   if (!(eps_std >= 0.f)) return AT_GRPO_EINVAL;
   WsAlloc ws(workspace);
   GaPlan p;
-  if (!plan(n_resp, n_env, n_agent, n_turn, ws, &p)) return AT_GRPO_EUNSUPPORTED;
+  if (!plan(n_resp, n_env, n_agent, n_turn, group_by, n_sample, ws, &p)) return AT_GRPO_EUNSUPPORTED;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < ws.bytes())
     return AT_GRPO_EWORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -644,7 +687,8 @@ int run_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t 
 
   if (p.n_keys <= kSingleMaxKeys && n_resp <= kSingleMaxResp) {
     const GaMix mix{r_team, r_loc, alpha, reward_out};
-    const GaArgs a1{n_resp, n_env, n_agent, n_turn, env_id, agent_id, turn_id, r_team ? reward_out : reward};
+    const GaArgs a1{n_resp, n_env, n_agent, n_turn, env_id, agent_id, turn_id, r_team ? reward_out : reward,
+                    group_by, n_sample, sample_id};
     const GaStat st1{eps_std, ddof, norm};
     hipLaunchKernelGGL(k_ga_single, dim3(1), dim3(kSingleThreads), 0, s, a1, mix, st1, static_cast<int>(p.n_keys),
                        p.err, p.key_of_resp, p.rank_of_resp, p.arrival, group_id, n_groups, seg_offsets, perm, adv,
@@ -659,7 +703,7 @@ int run_group_advantage(int32_t n_resp, int32_t n_env, int32_t n_agent, int32_t 
     ATG_LAUNCH_CHECK();
     reward = reward_out;
   }
-  const GaArgs a{n_resp, n_env, n_agent, n_turn, env_id, agent_id, turn_id, reward};
+  const GaArgs a{n_resp, n_env, n_agent, n_turn, env_id, agent_id, turn_id, reward, group_by, n_sample, sample_id};
   const GaStat st{eps_std, ddof, norm};
   const unsigned rb = static_cast<unsigned>(ceil_div(n_resp, 256));
   const unsigned kb = static_cast<unsigned>(p.n_blocks);
@@ -731,6 +775,29 @@ extern "C" int at_grpo_group_advantage_mixed(int32_t n_resp, int32_t n_env, int3
                              r_loc, alpha, reward, best, workspace, workspace_bytes, hip_stream);
 }
 
+
+extern "C" int at_grpo_group_advantage_keyed(int32_t group_by, int32_t n_resp, int32_t n_env, int32_t n_agent,
+                                             int32_t n_turn, int32_t n_sample, const int32_t* env_id,
+                                             const int32_t* agent_id, const int32_t* turn_id,
+                                             const int32_t* sample_id, const float* reward, float eps_std,
+                                             int32_t ddof, int32_t norm, int32_t* group_id, int32_t* n_groups,
+                                             int32_t* seg_offsets, int32_t* perm, float* adv, float* group_mean,
+                                             float* group_std, void* workspace, size_t workspace_bytes,
+                                             void* hip_stream) {
+  if (!reward) return AT_GRPO_EINVAL;
+  return run_group_advantage(n_resp, n_env, n_agent, n_turn, env_id, agent_id, turn_id, reward, eps_std, ddof,
+                             norm, group_id, n_groups, seg_offsets, perm, adv, group_mean, group_std, nullptr,
+                             nullptr, 0.f, nullptr, nullptr, workspace, workspace_bytes, hip_stream, group_by,
+                             sample_id, n_sample);
+}
+
+extern "C" size_t at_grpo_group_advantage_keyed_workspace_bytes(int32_t group_by, int32_t n_resp, int32_t n_env,
+                                                                int32_t n_agent, int32_t n_turn, int32_t n_sample) {
+  if (group_by != AT_GRPO_GROUP_BY_AGENT_TURN && group_by != AT_GRPO_GROUP_BY_TRAJECTORY &&
+      group_by != AT_GRPO_GROUP_BY_PARALLEL)
+    return 0;
+  return group_advantage_workspace(n_resp, n_env, n_agent, n_turn, group_by, n_sample);
+}
 
 // ------------------------------------------------------------------------------------------------
 // The same call for callers that cannot allocate or hand over device scratch: the workspace is a

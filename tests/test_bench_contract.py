@@ -23,5 +23,5 @@ def test_recorded_traffic_is_tied_to_the_kernel_sources():
     if rec["source_digest"] == bench.kernel_source_digest():
         assert got == rec["kernels"]["k_head_dz"]["hbm_bytes_per_launch"]
     else:
-        assert got is None                  # counters taken on other code are not quoted
+        assert isinstance(got, str) and got.startswith("stale")     # counters taken on other code are not quoted
     assert bench.recorded_traffic("C9", "head_dz") is None

@@ -254,6 +254,78 @@ def test_group_advantage_flags_ids_out_of_range(gpu_device):
     assert int(out["group_id"][3].item()) == -1 and float(out["adv"][3].item()) == 0.0
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("group_by", ["trajectory", "parallel", "agent_turn"])
+@pytest.mark.parametrize("name", ["C4", "C2"])
+def test_group_advantage_under_the_other_keys(gpu_device, name, group_by):
+    """Trajectory-level groups (every candidate of a task, Sec. 5.3) and the groups parallel sampling
+    leaves (one response each after the first turn, Sec. 4.1) at the configurations' real sizes:
+    integers bit-exact, advantages as for the paper's key; C4 takes the multi-launch path, C2 the
+    one-workgroup path."""
+    cfg = synth.CONFIGS[name]
+    st = synth.make_structure(cfg)
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(gpu_device)
+    say(f"[group_advantage_keyed] {name} {group_by} R={cfg.n_resp}")
+    out = api.at_grpo_group_advantage_keyed(group_by, i32(st.env_id), i32(st.agent_id), i32(st.turn_id),
+                                            torch.from_numpy(st.reward).to(gpu_device), cfg.E, cfg.N, cfg.T,
+                                            sample_id=i32(st.sample_id), n_sample=cfg.K)
+    torch.cuda.synchronize()
+    assert api.error_word(out["workspace"]) == 0
+    key = orc.group_key_by(st.env_id, st.agent_id, st.turn_id, st.sample_id, cfg.N, cfg.T, cfg.K, group_by)
+    gid, G, offs, perm = orc.group_segments(key)
+    adv, mean, std = orc.group_advantage(st.reward, gid, G)
+    assert int(out["n_groups"]) == G
+    assert np.array_equal(host(out["group_id"]), gid)
+    assert np.array_equal(host(out["seg_offsets"])[:G + 1], offs)
+    assert np.array_equal(host(out["perm"]), perm)
+    got = host(out["adv"]).astype(np.float64)
+    assert np.all(got[std[gid] == 0] == 0) and np.allclose(got, adv, rtol=1e-4, atol=1e-6)
+    assert np.allclose(host(out["group_mean"])[:G], mean, rtol=1e-4, atol=1e-7)
+    assert np.allclose(host(out["group_std"])[:G], std, rtol=1e-4, atol=1e-7)
+    if group_by == "parallel":
+        assert np.all(got[st.turn_id > 0] == 0) and np.abs(got[st.turn_id == 0]).max() > 0
+    if group_by == "trajectory":
+        assert G == cfg.E
+    if group_by == "agent_turn":
+        plain = api.at_grpo_group_advantage(i32(st.env_id), i32(st.agent_id), i32(st.turn_id),
+                                            torch.from_numpy(st.reward).to(gpu_device), cfg.E, cfg.N, cfg.T)
+        torch.cuda.synchronize()
+        assert torch.equal(plain["adv"], out["adv"]) and torch.equal(plain["perm"], out["perm"])
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["C1", "C4"])
+def test_group_advantage_non_finite_rewards_take_no_part(gpu_device, name):
+    """A NaN and an infinite reward raise the data flag and drop out: no group id, advantage 0, and the
+    rest of their groups is what the oracle gives without them (both launch shapes)."""
+    cfg = synth.CONFIGS[name]
+    st = synth.make_structure(cfg)
+    reward = st.reward.copy()
+    bad = np.array([3, cfg.n_resp - 2])
+    reward[bad[0]] = np.nan
+    reward[bad[1]] = np.inf
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(gpu_device)
+    say(f"[group_advantage] {name}: non-finite rewards at {bad.tolist()}")
+    out = api.at_grpo_group_advantage(i32(st.env_id), i32(st.agent_id), i32(st.turn_id),
+                                      torch.from_numpy(reward).to(gpu_device), cfg.E, cfg.N, cfg.T)
+    torch.cuda.synchronize()
+    assert api.error_word(out["workspace"]) == 2
+    keep = np.ones(cfg.n_resp, bool)
+    keep[bad] = False
+    kept = np.nonzero(keep)[0]
+    key = orc.group_key(st.env_id[kept], st.agent_id[kept], st.turn_id[kept], cfg.N, cfg.T)
+    gid, G, offs, perm = orc.group_segments(key)
+    adv, mean, std = orc.group_advantage(reward[kept], gid, G)
+    got_gid, got_adv = host(out["group_id"]), host(out["adv"]).astype(np.float64)
+    assert np.all(got_gid[bad] == -1) and np.all(got_adv[bad] == 0)
+    assert int(out["n_groups"]) == G
+    assert np.array_equal(got_gid[kept], gid)
+    assert np.array_equal(host(out["seg_offsets"])[:G + 1], offs)
+    assert np.array_equal(host(out["perm"])[:kept.size], kept[perm])
+    assert np.all(np.isfinite(got_adv)) and np.allclose(got_adv[kept], adv, rtol=1e-4, atol=1e-6)
+    assert np.allclose(host(out["group_mean"])[:G], mean, rtol=1e-4, atol=1e-7)
+
+
 # ---------------------------------------------------------------------------- S3..S8 on oracle-sized cases
 def mini_cfg(name):
     """Oracle-sized twins: same heads, H, layout and reward structure as the named config.  C2 keeps

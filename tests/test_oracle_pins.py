@@ -854,3 +854,50 @@ def test_gradient_comparison_catches_planted_mistakes():
     bad_h[live[int(np.argsort(hn)[len(hn) // 10])]] = 0.0           # one light token row of d_hidden lost
     assert helpers.rel_fro(bad_h, dH) < tol
     fails(bad_h, dH)
+
+
+# ------------------------------------------------------------------ the other grouping keys
+def test_trajectory_and_parallel_keys_by_brute_force():
+    """Trajectory-level groups hold every response of a task, mixing agents and turns; parallel
+    sampling leaves full groups at the first turn and groups of one after it, whose advantage is 0
+    exactly, while its first-turn advantages are those of the agent- and turn-wise grouping."""
+    cfg = replace(synth.CONFIGS["C1"], E=5, N=3, T=4, K=4, reward_kind="uniform", forced_equal_groups=0,
+                  seed=synth.BASE_SEED + 500)
+    st = synth.make_structure(cfg)
+    R = cfg.n_resp
+    # trajectory: brute force over pairs
+    key = orc.group_key_by(st.env_id, st.agent_id, st.turn_id, st.sample_id, cfg.N, cfg.T, cfg.K, "trajectory")
+    gid, G, offs, perm = orc.group_segments(key)
+    assert G == cfg.E
+    for a in range(R):
+        for b in range(R):
+            assert (gid[a] == gid[b]) == (st.env_id[a] == st.env_id[b])
+    assert np.all(np.diff(offs) == cfg.N * cfg.T * cfg.K)
+    members = perm[offs[2]:offs[3]]
+    assert len(set(st.agent_id[members])) == cfg.N and len(set(st.turn_id[members])) == cfg.T   # mixed states
+    assert gid[members[0]] == sorted(set(st.env_id.tolist())).index(int(st.env_id[members[0]]))
+    adv, _, _ = orc.group_advantage(st.reward, gid, G)
+    for g in range(G):
+        assert abs(adv[gid == g].sum()) < 1e-9
+    # parallel sampling
+    key = orc.group_key_by(st.env_id, st.agent_id, st.turn_id, st.sample_id, cfg.N, cfg.T, cfg.K, "parallel")
+    gid_p, G_p, offs_p, perm_p = orc.group_segments(key)
+    assert G_p == cfg.E * cfg.N * (1 + (cfg.T - 1) * cfg.K)
+    for a in range(R):
+        for b in range(R):
+            same = (st.env_id[a], st.agent_id[a], st.turn_id[a]) == (st.env_id[b], st.agent_id[b], st.turn_id[b]) \
+                and (st.turn_id[a] == 0 or st.sample_id[a] == st.sample_id[b])
+            assert (gid_p[a] == gid_p[b]) == same
+    adv_p, _, _ = orc.group_advantage(st.reward, gid_p, G_p)
+    assert np.all(adv_p[st.turn_id > 0] == 0.0)
+    key_at = orc.group_key_by(st.env_id, st.agent_id, st.turn_id, None, cfg.N, cfg.T, cfg.K, "agent_turn")
+    assert np.array_equal(key_at, orc.group_key(st.env_id, st.agent_id, st.turn_id, cfg.N, cfg.T))
+    gid_at, G_at, _, _ = orc.group_segments(key_at)
+    adv_at, _, _ = orc.group_advantage(st.reward, gid_at, G_at)
+    first = st.turn_id == 0
+    assert np.array_equal(adv_p[first], adv_at[first]) and np.abs(adv_at[~first]).max() > 0
+    # ascending key is the lexicographic order of the tuple
+    order = np.argsort(key, kind="stable")
+    tuples = [(int(st.env_id[r]), int(st.agent_id[r]), int(st.turn_id[r]),
+               int(st.sample_id[r]) if st.turn_id[r] > 0 else 0) for r in order]
+    assert tuples == sorted(tuples)
