@@ -25,7 +25,14 @@ if ROOT not in sys.path:
 from paper_2510_11062_amd import api, synth, workload  # noqa: E402
 
 PEAK = {"bf16": 2500.0, "f32": 157.3}      # dense MFMA TFLOP/s, MI355X data sheet
-CHUNK_TOKENS = 32768                       # list positions one head-kernel launch covers
+def chunk_tokens(kern, cfg):
+    """List positions one launch of a head kernel class covers (the library's launch plan)."""
+    if kern == "head_dw":
+        return 32768
+    if kern == "head_fwd":
+        return 16384
+    row_bytes = cfg.H * (2 if cfg.dtype == "bf16" else 4)
+    return min(16384, (64 << 20) // row_bytes // 256 * 256)
 KERNEL_SYMBOL = {"head_fwd": "k_head_fwd", "head_dz": "k_head_dz", "head_dh": "k_head_dh", "head_dw": "k_head_dw"}
 
 
@@ -141,7 +148,7 @@ def run_config(cfg, dev, steps, warmup):
     # launches that had rows to process (the others return at once): per head, ceil(rows / chunk)
     live = valid if kern == "head_fwd" else grad_rows
     rows_per_head = torch.bincount(wl.head_of_tok[live], minlength=cfg.n_heads).tolist()
-    work_launches = sum(-(-r // CHUNK_TOKENS) for r in rows_per_head)
+    work_launches = sum(-(-r // chunk_tokens(kern, cfg)) for r in rows_per_head)
     peak = PEAK[cfg.dtype]
     all_gemm_ms = sum(prof[k][1] for k in flops) / steps
     all_gemm_tflops = sum(flops.values()) / (all_gemm_ms * 1e-3) / 1e12
