@@ -36,11 +36,12 @@ def chunk_tokens(kern, cfg):
 KERNEL_SYMBOL = {"head_fwd": "k_head_fwd", "head_dz": "k_head_dz", "head_dh": "k_head_dh", "head_dw": "k_head_dw"}
 
 
-HEAD_KERNEL_SOURCES = ("common.hpp", "gemm_core.hpp", "head_kernels.hpp", "head_kernels.hip")
+# the kernels and the launch plan (rows per launch) that decides what one launch moves
+HEAD_KERNEL_SOURCES = ("common.hpp", "gemm_core.hpp", "head_kernels.hpp", "head_kernels.hip", "api.hip")
 
 
 def kernel_source_digest():
-    """sha256 over the sources of the head kernels (the ones `traffic` is quoted for): HBM counter
+    """sha256 over the sources of the head kernels and of their launch plan (what `traffic` is quoted for): HBM counter
     readings are only reported for the code they were taken on."""
     import hashlib
     h = hashlib.sha256()

@@ -11,6 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libat_grpo.so")
 CLIENT = os.path.join(PKG, "abi_client")
+PROBE = os.path.join(PKG, "gemm_probe")
 SOURCES = ["api.hip", "group_advantage.hip", "token_kernels.hip", "head_kernels.hip", "optimizer.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -43,6 +44,15 @@ def build_client(verbose: bool = True) -> str:
     return CLIENT
 
 
+def build_probe(verbose: bool = True) -> str:
+    """The tile loops as plain GEMMs (measurement aid, see csrc/gemm_probe.hip and bench_gemm.py)."""
+    cmd = [HIPCC, *[f for f in FLAGS if f != "-fPIC"], os.path.join(CSRC, "gemm_probe.hip"), "-o", PROBE]
+    subprocess.run(cmd, check=True)
+    if verbose:
+        print("built", PROBE)
+    return PROBE
+
+
 def build(verbose: bool = True) -> str:
     with ThreadPoolExecutor(max_workers=4) as pool:
         objs = list(pool.map(_compile, SOURCES))
@@ -51,6 +61,7 @@ def build(verbose: bool = True) -> str:
     if verbose:
         print("built", LIB)
     build_client(verbose)
+    build_probe(verbose)
     return LIB
 
 
