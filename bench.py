@@ -31,9 +31,13 @@ def chunk_tokens(kern, cfg):
         return 32768
     if kern == "head_fwd":
         return 16384
+    # head_fe, head_dz, head_dh: the part of a super-chunk whose hidden rows fill 64 MB
     row_bytes = cfg.H * (2 if cfg.dtype == "bf16" else 4)
     return min(16384, (64 << 20) // row_bytes // 256 * 256)
-KERNEL_SYMBOL = {"head_fwd": "k_head_fwd", "head_dz": "k_head_dz", "head_dh": "k_head_dh", "head_dw": "k_head_dw"}
+
+
+KERNEL_SYMBOL = {"head_fwd": "k_head_fwd", "head_fe": "k_head_fe", "head_dz": "k_head_dz", "head_dh": "k_head_dh",
+                 "head_dw": "k_head_dw"}
 
 
 # the kernels and the launch plan (rows per launch) that decides what one launch moves
@@ -103,9 +107,11 @@ def cpu_baseline(cfg, st, batch, old_logp, n_sample):
             "extrapolated_full_workload_s": n_all / (n / dt)}
 
 
-def run_config(cfg, dev, steps, warmup):
+def run_config(cfg, dev, steps, warmup, path="one_pass"):
     """Times `steps` steps (grouped advantages + loss forward + backward) of one workload; returns the
-    measurements and what the caller needs for the CPU leg."""
+    measurements and what the caller needs for the CPU leg.  path: "one_pass" = at_grpo_policy_loss_fwd_bwd
+    (logits produced once), "two_calls" = at_grpo_policy_loss_fwd then at_grpo_policy_loss_bwd (logits
+    recomputed by the backward)."""
     wl = workload.build(cfg, dev)
     st, batch, old_logp, resp_of_tok, valid = wl.st, wl.batch, wl.old_logp, wl.resp_of_tok, wl.valid
     env_id, agent_id, turn_id, reward = wl.env_id, wl.agent_id, wl.turn_id, wl.reward
@@ -116,9 +122,13 @@ def run_config(cfg, dev, steps, warmup):
 
     def step():
         ga = api.at_grpo_group_advantage(env_id, agent_id, turn_id, reward, cfg.E, cfg.N, cfg.T, want_stats=False)
-        fwd = api.at_grpo_policy_loss_fwd(batch, old_logp, ga["adv"], eps, eps, out=state.get("fwd"))
-        api.at_grpo_policy_loss_bwd(batch, old_logp, ga["adv"], fwd["logp"], fwd["lse"], eps, eps,
-                                    dW=dW, d_hidden=d_hidden)
+        if path == "one_pass":
+            fwd = api.at_grpo_policy_loss_fwd_bwd(batch, old_logp, ga["adv"], eps, eps, dW=dW, d_hidden=d_hidden,
+                                                  out=state.get("fwd"))
+        else:
+            fwd = api.at_grpo_policy_loss_fwd(batch, old_logp, ga["adv"], eps, eps, out=state.get("fwd"))
+            api.at_grpo_policy_loss_bwd(batch, old_logp, ga["adv"], fwd["logp"], fwd["lse"], eps, eps,
+                                        dW=dW, d_hidden=d_hidden)
         state["fwd"], state["ga"] = fwd, ga
 
     for _ in range(warmup):
@@ -142,12 +152,23 @@ def run_config(cfg, dev, steps, warmup):
     grad_rows = valid & (A_tok != 0) & ((fwd["clip_mask"] & 4) == 0)
     n_grad = int(grad_rows.sum().item())
     hv2 = 2.0 * cfg.H * cfg.V
-    flops = {"head_fwd": hv2 * n_valid, "head_dz": hv2 * n_grad, "head_dh": hv2 * n_grad, "head_dw": hv2 * n_grad}
+    if path == "one_pass":
+        # rows of non-zero advantage get their logits once (head_fe), the others only their log-probability
+        # (head_fwd); the two backward contractions run over the first class and are credited with the rows that
+        # carry gradient (the clipped ones among them multiply by a zero factor)
+        adv_rows = valid & (A_tok != 0)
+        n_adv = int(adv_rows.sum().item())
+        flops = {"head_fwd": hv2 * (n_valid - n_adv), "head_fe": hv2 * n_adv, "head_dh": hv2 * n_grad,
+                 "head_dw": hv2 * n_grad}
+        rows_of = {"head_fwd": valid & ~adv_rows, "head_fe": adv_rows, "head_dh": adv_rows, "head_dw": adv_rows}
+    else:
+        flops = {"head_fwd": hv2 * n_valid, "head_dz": hv2 * n_grad, "head_dh": hv2 * n_grad, "head_dw": hv2 * n_grad}
+        rows_of = {"head_fwd": valid, "head_dz": grad_rows, "head_dh": grad_rows, "head_dw": grad_rows}
     kern = max(flops, key=lambda k: prof[k][1])
     kern_ms = prof[kern][1] / steps
     achieved = flops[kern] / (kern_ms * 1e-3) / 1e12
     # launches that had rows to process (the others return at once): per head, ceil(rows / chunk)
-    live = valid if kern == "head_fwd" else grad_rows
+    live = rows_of[kern]
     rows_per_head = torch.bincount(wl.head_of_tok[live], minlength=cfg.n_heads).tolist()
     work_launches = sum(-(-r // chunk_tokens(kern, cfg)) for r in rows_per_head)
     peak = PEAK[cfg.dtype]
@@ -159,7 +180,9 @@ def run_config(cfg, dev, steps, warmup):
                     f"{n_valid} response tokens in {st.n_tok} rows"
                     f"{' (padded + mask)' if cfg.padded else ' (packed)'}",
         "tokens_per_s": n_valid / (elapsed / steps), "ms_per_step": elapsed / steps * 1e3, "steps": steps,
-        "response_tokens": n_valid, "rows_with_gradient": n_grad, "device_error_word": err,
+        "response_tokens": n_valid, "rows_with_gradient": n_grad, "device_error_word": err, "path": path,
+        "executed_flop_per_step": sum(flops.values()),
+        "flop_per_step_if_logits_were_recomputed": hv2 * (n_valid + 3 * n_grad),
         "roofline": {"bound": "mfma", "kernel": kern, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": recorded_traffic(cfg.name, kern),
                      "flop_per_launch": flops[kern] / max(work_launches, 1),
@@ -168,7 +191,7 @@ def run_config(cfg, dev, steps, warmup):
                      "kernel_ms_per_step": kern_ms, "launches_per_step": prof[kern][0] / steps,
                      "all_head_contractions_tflops": all_gemm_tflops,
                      "all_head_contractions_frac": all_gemm_tflops / peak},
-        "head_kernel_tflops": {k: flops[k] / (prof[k][1] / steps * 1e-3) / 1e12 for k in flops},
+        "head_kernel_tflops": {k: flops[k] / (prof[k][1] / steps * 1e-3) / 1e12 for k in flops if prof[k][1] > 0},
         "kernel_ms_per_step": {k: v[1] / steps for k, v in prof.items()},
     }
     return rec, (st, batch, old_logp)
@@ -201,6 +224,8 @@ def main():
                     help="further workloads timed after it and reported under `configs` ('none' to skip)")
     ap.add_argument("--more-steps", type=int, default=3, help="timed steps of each further workload")
     ap.add_argument("--no-streaming", action="store_true", help="skip the bandwidth records of the streaming kernels")
+    ap.add_argument("--path", default="one_pass", choices=["one_pass", "two_calls"],
+                    help="one_pass: at_grpo_policy_loss_fwd_bwd; two_calls: forward call, then backward call")
     ap.add_argument("--cpu-sample", type=int, default=6144, help="response tokens given to the CPU oracle (0 = skip)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 1 GiB with torch (known traffic, to scale HBM counters)")
@@ -216,7 +241,7 @@ def main():
     cfg = synth.CONFIGS[args.config]
     api.load_library()
 
-    rec, (st, batch, old_logp) = run_config(cfg, dev, args.steps, args.warmup)
+    rec, (st, batch, old_logp) = run_config(cfg, dev, args.steps, args.warmup, args.path)
 
     if args.calibration_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -231,7 +256,7 @@ def main():
         "ms_per_step": rec["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": rec["workload"], "rows_with_gradient": rec["rows_with_gradient"],
-                   "device_error_word": rec["device_error_word"]},
+                   "device_error_word": rec["device_error_word"], "path": rec["path"]},
         "roofline": rec["roofline"],
         "head_kernel_tflops": rec["head_kernel_tflops"],
         "kernel_ms_per_step": rec["kernel_ms_per_step"],
@@ -245,7 +270,7 @@ def main():
     if args.more_configs.lower() != "none":
         out["configs"] = {}
         for name in [c for c in args.more_configs.split(",") if c and c != args.config]:
-            more, keep = run_config(synth.CONFIGS[name], dev, args.more_steps, 1)
+            more, keep = run_config(synth.CONFIGS[name], dev, args.more_steps, 1, args.path)
             more.pop("kernel_ms_per_step")
             out["configs"][name] = more
             del keep

@@ -86,7 +86,8 @@ typedef enum {
   AT_GRPO_CALL_SURROGATE = 4,
   AT_GRPO_CALL_HEAD_UPDATE = 5,  /* size does not depend on the other arguments */
   AT_GRPO_CALL_DIAGNOSTICS = 6,
-  AT_GRPO_CALL_TOKEN_ENTROPY = 7
+  AT_GRPO_CALL_TOKEN_ENTROPY = 7,
+  AT_GRPO_CALL_POLICY_LOSS_FWD_BWD = 8
 } at_grpo_call;
 
 /*
@@ -281,6 +282,27 @@ int at_grpo_policy_loss_bwd(const at_grpo_batch* batch, const float* old_logp, c
                             float eps_low, float eps_high, int32_t agg, const float* grad_loss,
                             void* d_hidden, float* const* dW, int32_t accumulate_dW,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * One training step's worth of Eq. (2): at_grpo_policy_loss_fwd followed by at_grpo_policy_loss_bwd
+ * (same arguments, same outputs, same error behaviour), computed from ONE pass over the logits.  For
+ * AT_GRPO_BF16, rows whose response has a non-zero advantage (only they can carry gradient) have their
+ * logits produced once: with the reference c_t = z[t, token_id[t]] (one dot product per row) the forward
+ * tile writes e[t, v] = exp(z[t, v] - c_t) in bf16, as dZ would be written, and
+ *   lse_t = c_t + ln S_t,  S_t = sum_v e[t, v],   dZ[t, v] = a_t (e[t, v] - S_t 1[v = token_id[t]]),
+ *   a_t = -g_t / S_t
+ * so that d_hidden and dW follow from e by two contractions and a per-row factor, without recomputing the
+ * logits.  A launch in which some S_t leaves [1, 2^60) (the sampled token about e^88 times less likely than
+ * the mode, or non-finite inputs) is redone by the two-pass kernels, on the device, without host
+ * involvement.  Rows of zero-advantage responses only get logp / lse.  AT_GRPO_F32 runs the two calls one
+ * after the other.  Results agree with the two-call sequence to rounding (e and the scaled hidden rows are
+ * rounded to bf16 where that path rounds dZ).  Workspace: AT_GRPO_CALL_POLICY_LOSS_FWD_BWD.
+ */
+int at_grpo_policy_loss_fwd_bwd(const at_grpo_batch* batch, const float* old_logp, const float* adv,
+                                float eps_low, float eps_high, int32_t agg, const float* grad_loss,
+                                float* loss, float* logp, float* lse, uint8_t* clip_mask, int32_t* n_valid,
+                                void* d_hidden, float* const* dW, int32_t accumulate_dW,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Hyper-parameters of the head update (App. C.1: Adam, learning rate 1e-6, weight decay 0.01,

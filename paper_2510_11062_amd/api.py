@@ -21,7 +21,7 @@ AGG = {"token_mean": 0, "seq_mean_token_mean": 1}
 NORM = {"std": 0, "none": 1}
 GROUP_BY = {"agent_turn": 0, "trajectory": 1, "parallel": 2}
 CALL_GROUP_ADVANTAGE, CALL_TOKEN_LOGPROB, CALL_POLICY_LOSS_FWD, CALL_POLICY_LOSS_BWD, CALL_SURROGATE, \
-    CALL_HEAD_UPDATE, CALL_DIAGNOSTICS, CALL_TOKEN_ENTROPY = range(8)
+    CALL_HEAD_UPDATE, CALL_DIAGNOSTICS, CALL_TOKEN_ENTROPY, CALL_POLICY_LOSS_FWD_BWD = range(9)
 DTYPE = {torch.float32: 0, torch.bfloat16: 1}
 
 EXPORTS = [
@@ -29,7 +29,7 @@ EXPORTS = [
     "at_grpo_group_advantage_keyed", "at_grpo_group_advantage_keyed_workspace_bytes",
     "at_grpo_static_scratch_bytes", "at_grpo_token_logprob", "at_grpo_surrogate_from_logp",
     "at_grpo_surrogate_diagnostics", "at_grpo_token_entropy",
-    "at_grpo_policy_loss_fwd", "at_grpo_policy_loss_bwd", "at_grpo_head_update", "at_grpo_workspace_bytes",
+    "at_grpo_policy_loss_fwd", "at_grpo_policy_loss_bwd", "at_grpo_policy_loss_fwd_bwd", "at_grpo_head_update", "at_grpo_workspace_bytes",
     "at_grpo_status_string", "at_grpo_version", "at_grpo_profile_enable", "at_grpo_profile_classes",
     "at_grpo_profile_read",
 ]
@@ -104,6 +104,9 @@ def load_library():
     lib.at_grpo_policy_loss_bwd.argtypes = [C.POINTER(_Batch), vp, vp, vp, vp, f32, f32, i32, vp, vp,
                                             C.POINTER(C.c_void_p), i32, vp, sz, vp]
     lib.at_grpo_policy_loss_bwd.restype = C.c_int
+    lib.at_grpo_policy_loss_fwd_bwd.argtypes = [C.POINTER(_Batch), vp, vp, f32, f32, i32, vp, vp, vp, vp, vp, vp,
+                                                vp, C.POINTER(C.c_void_p), i32, vp, sz, vp]
+    lib.at_grpo_policy_loss_fwd_bwd.restype = C.c_int
     lib.at_grpo_workspace_bytes.argtypes = [i32, C.POINTER(_Batch), i32, i32, i32, i32]
     lib.at_grpo_workspace_bytes.restype = sz
     lib.at_grpo_status_string.argtypes = [i32]
@@ -518,6 +521,48 @@ def at_grpo_policy_loss_bwd(batch: Batch, old_logp, adv, logp, lse, eps_low: flo
                                      _ptr(ws), ws.numel(), _stream())
     _check(st, "at_grpo_policy_loss_bwd")
     return dict(d_hidden=d_hidden, dW=dW, workspace=ws)
+
+
+def at_grpo_policy_loss_fwd_bwd(batch: Batch, old_logp, adv, eps_low: float, eps_high: float,
+                                agg: str = "token_mean", grad_loss=None, dW: Optional[List[torch.Tensor]] = None,
+                                accumulate_dW: bool = False, d_hidden: Optional[torch.Tensor] = None,
+                                out: Optional[dict] = None):
+    """Forward and backward of the policy loss from one pass over the logits; returns the outputs of both."""
+    lib = load_library()
+    cb = batch.to_c()
+    _dev_check(old_logp, adv, grad_loss, d_hidden)
+    _f32_check(old_logp=old_logp, adv=adv, grad_loss=grad_loss)
+    if d_hidden is not None and (d_hidden.dtype != batch.hidden.dtype or d_hidden.shape != batch.hidden.shape):
+        raise AtGrpoError("d_hidden must have hidden's dtype and shape")
+    dev = batch.hidden.device
+    if out is None:
+        out = dict(
+            loss=torch.empty(cb.n_heads, dtype=torch.float32, device=dev),
+            logp=torch.empty(cb.n_tok, dtype=torch.float32, device=dev),
+            lse=torch.empty(cb.n_tok, dtype=torch.float32, device=dev),
+            clip_mask=torch.empty(cb.n_tok, dtype=torch.uint8, device=dev),
+            n_valid=torch.empty(cb.n_heads, dtype=torch.int32, device=dev),
+        )
+    if d_hidden is None:
+        d_hidden = torch.empty_like(batch.hidden)
+    if dW is None:
+        if accumulate_dW:
+            raise AtGrpoError("accumulate_dW needs dW tensors")
+        dW = [torch.empty(w.shape, dtype=torch.float32, device=dev) for w in batch.W]
+    for g in dW:
+        _dev_check(g)
+        if g.dtype != torch.float32:
+            raise AtGrpoError("dW must be float32")
+    dw_array = (C.c_void_p * len(dW))(*[g.data_ptr() for g in dW])
+    ws = _workspace(lib.at_grpo_workspace_bytes(CALL_POLICY_LOSS_FWD_BWD, C.byref(cb), 0, 0, 0, 0), dev)
+    st = lib.at_grpo_policy_loss_fwd_bwd(C.byref(cb), _ptr(old_logp), _ptr(adv), eps_low, eps_high, AGG[agg],
+                                         _ptr(grad_loss), _ptr(out["loss"]), _ptr(out["logp"]), _ptr(out["lse"]),
+                                         _ptr(out["clip_mask"]), _ptr(out["n_valid"]), _ptr(d_hidden),
+                                         C.cast(dw_array, C.POINTER(C.c_void_p)), 1 if accumulate_dW else 0,
+                                         _ptr(ws), ws.numel(), _stream())
+    _check(st, "at_grpo_policy_loss_fwd_bwd")
+    out.update(d_hidden=d_hidden, dW=dW, workspace=ws)
+    return out
 
 
 def error_word(workspace: torch.Tensor) -> int:

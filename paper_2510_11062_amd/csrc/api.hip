@@ -20,7 +20,7 @@ struct ProfState {
 ProfState g_prof;
 const char* const kProfNames[PROF_N] = {"group_advantage", "token_prep", "head_fwd", "lse_combine",
                                         "surrogate", "coef", "transpose", "head_dz", "head_dh",
-                                        "head_dw", "fill", "grad_norm", "adam"};
+                                        "head_dw", "fill", "grad_norm", "adam", "head_fe"};
 }  // namespace
 
 void prof_begin(int cls, hipStream_t s) {
@@ -76,6 +76,13 @@ struct Plan {
   void* hT;
   void* dZ;
   void* dZt;
+  // one-pass forward + backward only
+  TokenScratch SB, SF;   // the rows that can carry gradient / the rows with a zero advantage (own flag, cnt, idx)
+  HeadGeom gF;           // geometry of the log-probability-only launches
+  float* c2;             // [sub] reference of the exponentials
+  float* scale;          // [TC] row factors of the super-chunk
+  int32_t* gates;        // one word per launch of the exponentials
+  int n_gates;
 };
 
 int check_layout(const at_grpo_batch* b, bool need_tensors) {
@@ -144,7 +151,8 @@ void make_plan(const at_grpo_batch* b, int call, WsAlloc& ws, Plan* p) {
   g.Vp = static_cast<int>(round_up(static_cast<size_t>(b->V), 64));
   g.n_vtiles = static_cast<int>(ceil_div(b->V, 256));
   int64_t tc = static_cast<int64_t>(round_up(static_cast<size_t>(n_tok), 256));
-  const bool bwd = call == AT_GRPO_CALL_POLICY_LOSS_BWD;
+  const bool step = call == AT_GRPO_CALL_POLICY_LOSS_FWD_BWD;
+  const bool bwd = call == AT_GRPO_CALL_POLICY_LOSS_BWD || step;
   const int64_t tc_max = bwd ? kMaxChunkTokens : kSubChunkTokens;
   if (tc > tc_max) tc = tc_max;
   if (bwd) {
@@ -170,8 +178,30 @@ void make_plan(const at_grpo_batch* b, int call, WsAlloc& ws, Plan* p) {
     p->part_u = call == AT_GRPO_CALL_TOKEN_ENTROPY ? ws.take<float>(np) : nullptr;
     p->zy = ws.take<float>(static_cast<size_t>(g.TC));
   }
-  if (call == AT_GRPO_CALL_POLICY_LOSS_BWD) {
-    p->coef = ws.take<float>(static_cast<size_t>(n_tok));
+  if (step) {
+    // a second compaction (flags, counts, lists) beside the one of S, whose list serves the other class
+    p->SB = S;
+    p->SF = S;
+    p->SB.flag = ws.take<int32_t>(static_cast<size_t>(n_tok));
+    p->SF.flag = ws.take<int32_t>(static_cast<size_t>(n_tok));
+    p->SB.cnt = ws.take<int32_t>(kMaxHeads);
+    p->SF.cnt = ws.take<int32_t>(kMaxHeads);
+    p->SF.idx = ws.take<int32_t>(static_cast<size_t>(M) * static_cast<size_t>(n_tok));
+    p->gF = g;
+    p->gF.TC = static_cast<int>(tc < kSubChunkTokens ? tc : kSubChunkTokens);
+    const size_t rows = static_cast<size_t>(p->sub > p->gF.TC ? p->sub : p->gF.TC);   // rows of the largest launch
+    const size_t np = static_cast<size_t>(g.n_vtiles) * rows;
+    p->part_m = ws.take<float>(np);
+    p->part_s = ws.take<float>(np);
+    p->part_u = nullptr;
+    p->zy = ws.take<float>(rows);
+    p->c2 = ws.take<float>(rows);
+    p->scale = ws.take<float>(static_cast<size_t>(g.TC));
+    p->n_gates = M * p->n_chunks * (g.TC / p->sub);
+    p->gates = ws.take<int32_t>(static_cast<size_t>(p->n_gates));
+  }
+  if (bwd) {
+    p->coef = step ? nullptr : ws.take<float>(static_cast<size_t>(n_tok));
     p->Wt = ws.take<char>(static_cast<size_t>(g.H) * g.Vp * g.esize);
     p->hT = ws.take<char>(static_cast<size_t>(g.H) * g.TC * g.esize);
     p->dZ = ws.take<char>(static_cast<size_t>(g.TC) * g.Vp * g.esize);
@@ -184,21 +214,28 @@ int check_workspace(void* workspace, size_t have, size_t need) {
   return AT_GRPO_OK;
 }
 
+// log-probabilities of the rows on the per-head lists of S, in launches of g.TC rows
+int enqueue_logprob_lists(const at_grpo_batch* b, const Plan& p, const HeadGeom& g, const TokenScratch& S,
+                          float* logp, float* lse, float* entropy, hipStream_t s) {
+  float* part_u = entropy ? p.part_u : nullptr;
+  const int n_chunks = static_cast<int>(ceil_div(p.L.n_tok, g.TC));
+  for (int m = 0; m < b->n_heads; ++m) {
+    for (int c = 0; c < n_chunks; ++c) {
+      const HeadChunk ch{S.idx + static_cast<size_t>(m) * p.L.n_tok, S.cnt + m, c * g.TC};
+      ATG_TRY(launch_head_fwd(g, ch, b->hidden, b->W[m], b->token_id, p.part_m, p.part_s, part_u, p.zy, s));
+      ATG_TRY(launch_lse_combine(g, ch, p.part_m, p.part_s, part_u, p.zy, logp, lse, entropy, s));
+    }
+  }
+  return AT_GRPO_OK;
+}
+
 int enqueue_logprob(const at_grpo_batch* b, const Plan& p, float* logp, float* lse, float* entropy,
                     hipStream_t s) {
   ATG_TRY(launch_route(p.L, p.S, s));
   ATG_TRY(launch_compact(p.L, p.S, true, s));
   ATG_TRY(launch_zero_nonparticipating(p.L, p.S, logp, lse, s));
   if (entropy) ATG_TRY(launch_zero_nonparticipating(p.L, p.S, entropy, nullptr, s));
-  float* part_u = entropy ? p.part_u : nullptr;
-  for (int m = 0; m < b->n_heads; ++m) {
-    for (int c = 0; c < p.n_chunks; ++c) {
-      const HeadChunk ch{p.S.idx + static_cast<size_t>(m) * p.L.n_tok, p.S.cnt + m, c * p.g.TC};
-      ATG_TRY(launch_head_fwd(p.g, ch, b->hidden, b->W[m], b->token_id, p.part_m, p.part_s, part_u, p.zy, s));
-      ATG_TRY(launch_lse_combine(p.g, ch, p.part_m, p.part_s, part_u, p.zy, logp, lse, entropy, s));
-    }
-  }
-  return AT_GRPO_OK;
+  return enqueue_logprob_lists(b, p, p.g, p.S, logp, lse, entropy, s);
 }
 
 bool agg_ok(int agg) { return agg == AT_GRPO_AGG_TOKEN_MEAN || agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN; }
@@ -219,8 +256,14 @@ extern "C" size_t at_grpo_workspace_bytes(int32_t which_call, const at_grpo_batc
     return diagnostics_workspace(batch->n_resp);
   }
   if ((which_call < AT_GRPO_CALL_TOKEN_LOGPROB || which_call > AT_GRPO_CALL_SURROGATE) &&
-      which_call != AT_GRPO_CALL_TOKEN_ENTROPY)
+      which_call != AT_GRPO_CALL_TOKEN_ENTROPY && which_call != AT_GRPO_CALL_POLICY_LOSS_FWD_BWD)
     return 0;
+  if (which_call == AT_GRPO_CALL_POLICY_LOSS_FWD_BWD && batch && batch->dtype == AT_GRPO_F32) {
+    // fp32 runs the two calls one after the other in the same workspace
+    const size_t f = at_grpo_workspace_bytes(AT_GRPO_CALL_POLICY_LOSS_FWD, batch, n_resp, n_env, n_agent, n_turn);
+    const size_t w = at_grpo_workspace_bytes(AT_GRPO_CALL_POLICY_LOSS_BWD, batch, n_resp, n_env, n_agent, n_turn);
+    return f > w ? f : w;
+  }
   const bool tensors = which_call != AT_GRPO_CALL_SURROGATE;
   if (check_layout(batch, tensors) != AT_GRPO_OK) return 0;
   WsAlloc ws(nullptr);
@@ -349,6 +392,79 @@ extern "C" int at_grpo_policy_loss_bwd(const at_grpo_batch* batch, const float* 
     }
   }
   return AT_GRPO_OK;
+}
+
+extern "C" int at_grpo_policy_loss_fwd_bwd(const at_grpo_batch* batch, const float* old_logp, const float* adv,
+                                           float eps_low, float eps_high, int32_t agg, const float* grad_loss,
+                                           float* loss, float* logp, float* lse, uint8_t* clip_mask,
+                                           int32_t* n_valid, void* d_hidden, float* const* dW,
+                                           int32_t accumulate_dW, void* workspace, size_t workspace_bytes,
+                                           void* hip_stream) {
+  ATG_TRY(check_layout(batch, true));
+  ATG_TRY(check_pointers(batch, true));
+  if (!old_logp || !adv || !loss || !logp || !lse || !d_hidden || !dW) return AT_GRPO_EINVAL;
+  if (reinterpret_cast<uintptr_t>(d_hidden) & 15) return AT_GRPO_EINVAL;
+  for (int m = 0; m < batch->n_heads; ++m)
+    if (!dW[m]) return AT_GRPO_EINVAL;
+  if (!agg_ok(agg) || !eps_ok(eps_low, eps_high)) return AT_GRPO_EINVAL;
+  if (batch->dtype == AT_GRPO_F32) {
+    ATG_TRY(at_grpo_policy_loss_fwd(batch, old_logp, adv, eps_low, eps_high, agg, loss, logp, lse, clip_mask,
+                                    n_valid, workspace, workspace_bytes, hip_stream));
+    return at_grpo_policy_loss_bwd(batch, old_logp, adv, logp, lse, eps_low, eps_high, agg, grad_loss, d_hidden,
+                                   dW, accumulate_dW, workspace, workspace_bytes, hip_stream);
+  }
+  WsAlloc ws(workspace);
+  Plan p{};
+  make_plan(batch, AT_GRPO_CALL_POLICY_LOSS_FWD_BWD, ws, &p);
+  ATG_TRY(check_workspace(workspace, workspace_bytes, ws.bytes()));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  // participation; the weights of Eq. (2) count every participating row, whatever its advantage
+  ATG_TRY(launch_route(p.L, p.S, s));
+  ATG_TRY(launch_compact(p.L, p.S, false, s));
+  if (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN) ATG_TRY(launch_resp_len(p.L, p.S, s));
+  ATG_TRY(launch_zero_nonparticipating(p.L, p.S, logp, lse, s));
+  // rows of responses with a zero advantage carry no gradient: they only need their log-probability
+  ATG_TRY(launch_split_by_advantage(p.L, p.S, adv, p.SB.flag, p.SF.flag, s));
+  ATG_TRY(launch_compact(p.L, p.SF, true, s));
+  ATG_TRY(launch_compact(p.L, p.SB, true, s));
+  ATG_TRY(enqueue_logprob_lists(batch, p, p.gF, p.SF, logp, lse, nullptr, s));
+  ATG_TRY(launch_fill_bytes16(d_hidden, p.L.n_tok * static_cast<int64_t>(p.g.H) * p.g.esize, s));
+  ATG_TRY(launch_fill_i32(p.gates, p.n_gates, 0, s));
+  const CoefArgs ca = make_coef_args(p.S, old_logp, adv, eps_low, eps_high, agg, grad_loss);
+
+  int gate_no = 0;
+  for (int m = 0; m < batch->n_heads; ++m) {
+    ATG_TRY(launch_transpose_w(p.g, batch->W[m], p.Wt, s));
+    for (int c = 0; c < p.n_chunks; ++c) {
+      const HeadChunk ch{p.SB.idx + static_cast<size_t>(m) * p.L.n_tok, p.SB.cnt + m, c * p.g.TC};
+      HeadGeom gs = p.g;
+      gs.TC = p.sub;
+      for (int c1 = 0; c1 < p.g.TC; c1 += p.sub) {
+        const HeadChunk sub{ch.idx, ch.cnt, ch.c0 + c1};
+        char* E_sub = static_cast<char*>(p.dZ) + static_cast<size_t>(c1) * p.g.Vp * p.g.esize;
+        float* scale_sub = p.scale + c1;
+        int32_t* gate = p.gates + gate_no++;
+        ATG_TRY(launch_ref_logit(gs, sub, batch->hidden, batch->W[m], batch->token_id, p.c2, s));
+        ATG_TRY(launch_head_fe(gs, sub, batch->hidden, batch->W[m], batch->token_id, p.c2, E_sub, p.part_s, p.zy, s));
+        ATG_TRY(launch_fe_combine(gs, sub, m, p.part_s, p.c2, p.zy, batch->token_id, ca, logp, lse, scale_sub,
+                                  E_sub, gate, s));
+        // exponent range exceeded somewhere in this launch: the two-pass kernels redo it (they return at once
+        // otherwise)
+        ATG_TRY(launch_head_fwd(gs, sub, batch->hidden, batch->W[m], batch->token_id, p.part_m, p.part_s, nullptr,
+                                p.zy, s, gate));
+        ATG_TRY(launch_lse_combine(gs, sub, p.part_m, p.part_s, nullptr, p.zy, logp, lse, nullptr, s, gate));
+        ATG_TRY(launch_fallback_scale(gs, sub, m, ca, logp, scale_sub, gate, s));
+        ATG_TRY(launch_head_dz(gs, sub, batch->hidden, batch->W[m], batch->token_id, lse, nullptr, E_sub, nullptr, s,
+                               gate));
+        ATG_TRY(launch_head_dh(gs, sub, E_sub, p.Wt, d_hidden, s, scale_sub));
+      }
+      ATG_TRY(launch_gather_transpose_hidden(p.g, ch, batch->hidden, p.hT, s, p.scale));
+      ATG_TRY(launch_head_dw(p.g, ch, p.dZ, nullptr, p.hT, dW[m], (accumulate_dW != 0 || c > 0) ? 1 : 0,
+                             c == 0 ? 1 : 0, s));
+    }
+  }
+  return launch_surrogate(p.L, p.S, logp, old_logp, adv, eps_low, eps_high, agg, loss, clip_mask, n_valid, s);
 }
 
 extern "C" const char* at_grpo_status_string(int32_t status) {

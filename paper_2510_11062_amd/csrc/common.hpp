@@ -64,6 +64,7 @@ enum ProfClass {
   PROF_FILL,           // buffer clears
   PROF_GRAD_NORM,      // global gradient norm of the head update
   PROF_ADAM,           // fused clip + Adam step
+  PROF_HEAD_FE,        // head contraction that writes the exponentials (one-pass forward + backward)
   PROF_N
 };
 

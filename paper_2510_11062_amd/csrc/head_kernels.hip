@@ -14,6 +14,7 @@
 
 #include "gemm_core.hpp"
 #include "head_kernels.hpp"
+#include "token_kernels.hpp"
 
 namespace atg {
 
@@ -39,8 +40,9 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_fwd(
     const T* __restrict__ hidden, const T* __restrict__ W, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cnt, int c0, const int32_t* __restrict__ token_id,
     float* __restrict__ part_m, float* __restrict__ part_s, float* __restrict__ part_u,
-    float* __restrict__ zy, int H, int V, int TC, int n_vtiles) {
+    float* __restrict__ zy, int H, int V, int TC, int n_vtiles, const int32_t* __restrict__ gate) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  if (gate && *gate == 0) return;
   const int n = chunk_count(cnt, c0, TC);
   if (n <= 0) return;
   const TileOrder ord{n_vtiles, (n + kTile - 1) / kTile, 8};
@@ -180,8 +182,10 @@ __global__ __launch_bounds__(256) void k_lse_combine(const int32_t* __restrict__
                                                      const float* __restrict__ part_u,
                                                      const float* __restrict__ zy,
                                                      float* __restrict__ logp, float* __restrict__ lse,
-                                                     float* __restrict__ entropy) {
+                                                     float* __restrict__ entropy,
+                                                     const int32_t* __restrict__ gate) {
   __shared__ float sm[4][64], ss[4][64], su[4][64];
+  if (gate && *gate == 0) return;
   const int n = chunk_count(cnt, c0, TC);
   const int tx = threadIdx.x & 63, py = threadIdx.x >> 6;
   const int j = blockIdx.x * 64 + tx;
@@ -288,8 +292,9 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
     const T* __restrict__ hidden, const T* __restrict__ W, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cnt, int c0, const int32_t* __restrict__ token_id,
     const float* __restrict__ lse, const float* __restrict__ coef, T* __restrict__ dZ,
-    T* __restrict__ dZt, int H, int V, int Vp, int TC, int n_vtiles) {
+    T* __restrict__ dZt, int H, int V, int Vp, int TC, int n_vtiles, const int32_t* __restrict__ gate) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  if (gate && *gate == 0) return;
   const int n = chunk_count(cnt, c0, TC);
   if (n <= 0) return;
   const TileOrder ord{n_vtiles, (n + kTile - 1) / kTile, 8};
@@ -312,7 +317,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
       if (tcol[j] < n) {
         const int row = idx[c0 + tcol[j]];
         ycol[j] = token_id[row];
-        gcol[j] = coef[row];
+        gcol[j] = coef ? coef[row] : -1.f;   // without coefficients: softmax - onehot
         l2col[j] = lse[row] * kLog2e;
       } else {
         ycol[j] = -1;
@@ -412,6 +417,244 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dz(
 }
 
 // ------------------------------------------------------------------------------------------------
+// Forward and backward in one pass over the logits (bf16).  With a per-token reference c_t close
+// enough to the row's largest logit, e[t][v] = exp(z[t][v] - c_t) neither overflows nor loses the
+// terms that matter, and
+//   lse_t = c_t + ln S_t,  S_t = sum_v e[t][v],      softmax = e / S_t,
+//   dZ[t][v] = g_t (onehot - softmax) = a_t (e[t][v] - S_t [v = y_t]),  a_t = -g_t / S_t.
+// The forward tile therefore writes e once (bf16, as dZ would be written), the combine step patches
+// the one element per row that carries the onehot term, and the row factor a_t is applied where it is
+// cheap: to the accumulators of dHidden and to the gathered hidden rows that dW contracts with.  The
+// logits are not recomputed.  c_t is the target logit z[t][y_t] (one dot product per token): the
+// exponent then is ln(p_v / p_y), out of range only if the sampled token is ~e^88 times less likely
+// than the mode.  Rows for which S_t leaves [1, 2^60) are reported through a gate word, and the
+// caller then runs the two-pass kernels for that launch instead.
+// ------------------------------------------------------------------------------------------------
+constexpr float kMaxRefSum = 1152921504606846976.f;   // 2^60
+
+// c2[j] = log2(e) * <hidden[row_j], W[y_j]>: one wavefront per token of the launch
+__global__ __launch_bounds__(256) void k_ref_logit(const bf16_t* __restrict__ hidden, const bf16_t* __restrict__ W,
+                                                   const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
+                                                   int c0, int TC, const int32_t* __restrict__ token_id, int H,
+                                                   float* __restrict__ c2) {
+  const int n = chunk_count(cnt, c0, TC);
+  const int lane = threadIdx.x & 63;
+  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (j >= n) return;
+  const int row = idx[c0 + j];
+  const uint4* a = reinterpret_cast<const uint4*>(hidden + static_cast<size_t>(row) * H);
+  const uint4* b = reinterpret_cast<const uint4*>(W + static_cast<size_t>(token_id[row]) * H);
+  float acc = 0.f;
+  for (int c = lane; c < H / 8; c += 64) {
+    const uint4 x = a[c], y = b[c];
+    const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc = fmaf(__uint_as_float(xs[e] << 16), __uint_as_float(ys[e] << 16), acc);
+      acc = fmaf(__uint_as_float(xs[e] & 0xffff0000u), __uint_as_float(ys[e] & 0xffff0000u), acc);
+    }
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) c2[j] = acc * kLog2e;
+}
+
+constexpr int kFeLdsBytes = kDzLdsBytes + kWavesA * kTile * 4;   // staged tile, then the sums of the four vocabulary quarters
+
+// A = W rows (vocab -> accumulator registers), B = hidden rows (tokens -> lanes), as in the forward.
+// E[j][v] = exp(z - c_j) for the tokens j of the launch; part_s[vt][j] = sum over the 256 vocabulary rows
+// of tile vt; zy[j] = target logit.
+__global__ __launch_bounds__(kGemmThreads) void k_head_fe(
+    const bf16_t* __restrict__ hidden, const bf16_t* __restrict__ W, const int32_t* __restrict__ idx,
+    const int32_t* __restrict__ cnt, int c0, const int32_t* __restrict__ token_id,
+    const float* __restrict__ c2, bf16_t* __restrict__ E, float* __restrict__ part_s, float* __restrict__ zy,
+    int H, int V, int Vp, int TC, int n_vtiles) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int n = chunk_count(cnt, c0, TC);
+  if (n <= 0) return;
+  const TileOrder ord{n_vtiles, (n + kTile - 1) / kTile, 8};
+  const int total = ord.total();
+  const TileCoord tc;
+  const size_t row_bytes = static_cast<size_t>(H) * 2;
+  const int nk = static_cast<int>(row_bytes / kStepBytes);
+  float* red_s = reinterpret_cast<float*>(smem + kDzLdsBytes);   // [kWavesA][256]
+
+  for (int t = logical_workgroup(); t < total; t += gridDim.x) {
+    int vt, tt;
+    ord.decode(t, &vt, &tt);
+    const int v0 = vt * kTile, t0 = tt * kTile;
+
+    int tcol[kJB], ycol[kJB];
+    float nc2col[kJB];
+#pragma unroll
+    for (int j = 0; j < kJB; ++j) {
+      tcol[j] = t0 + tc.b_row(j);
+      if (tcol[j] < n) {
+        ycol[j] = token_id[idx[c0 + tcol[j]]];
+        nc2col[j] = -c2[tcol[j]];
+      } else {
+        ycol[j] = -1;
+        nc2col[j] = 0.f;
+      }
+    }
+
+    floatx16 acc[kIB][kJB];
+    gemm_tile<bf16_t>(
+        acc,
+        [&](int row) {
+          const int v = min(v0 + row, V - 1);
+          return reinterpret_cast<const char*>(W) + static_cast<size_t>(v) * row_bytes;
+        },
+        [&](int row) {
+          const int tk = min(t0 + row, n - 1);
+          return reinterpret_cast<const char*>(hidden) + static_cast<size_t>(idx[c0 + tk]) * row_bytes;
+        },
+        nk, smem);
+
+    constexpr int kWaveRows = kTile / kWavesA;
+    const int vwave = tc.wm * kWaveRows;             // first vocab row (inside the tile) of this wavefront
+    const int vbase = v0 + vwave;
+
+    // target logit: held by exactly one lane of one wavefront of one tile
+#pragma unroll
+    for (int j = 0; j < kJB; ++j) {
+      const int rel = ycol[j] - vbase;
+      const bool hit = (tcol[j] < n) && rel >= 0 && rel < kWaveRows && (((rel >> 2) & 1) == tc.half);
+      if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
+        float zt = 0.f;
+#pragma unroll
+        for (int i = 0; i < kIB; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int vl = i * 32 + 8 * (r >> 2) + (r & 3);   // half bit compared separately
+            if ((rel & ~4) == vl) zt = acc[i][j][r];
+          }
+        if (hit) zy[tcol[j]] = zt;
+      }
+    }
+
+    const bool interior = (v0 + kTile <= V) && (t0 + kTile <= n);
+    float csum[kJB];
+    auto emit = [&](auto guard_c) {
+      constexpr bool kGuard = decltype(guard_c)::value;
+#pragma unroll
+      for (int j = 0; j < kJB; ++j) {
+        const float nc2 = nc2col[j];
+        const bool live = tcol[j] < n;
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < kIB; ++i) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int vl = vwave + i * 32 + 8 * q + 4 * tc.half;   // first of 4 consecutive vocab rows
+            const int v = v0 + vl;
+            float d[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) d[e] = fast_exp2(fmaf(acc[i][j][q * 4 + e], kLog2e, nc2));
+            if (kGuard) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) d[e] = (v + e < V && live) ? d[e] : 0.f;   // k padding, rows past the count
+            }
+            sum += (d[0] + d[1]) + (d[2] + d[3]);
+            uint2 u;
+            u.x = pack_bf16x2(d[0], d[1]);
+            u.y = pack_bf16x2(d[2], d[3]);
+            *reinterpret_cast<uint2*>(smem + tc.b_row(j) * kDzRowStride + vl * 2) = u;
+          }
+        }
+        csum[j] = sum;
+      }
+    };
+    if (interior)
+      emit(std::false_type{});
+    else
+      emit(std::true_type{});
+#pragma unroll
+    for (int j = 0; j < kJB; ++j) {
+      const float sum = csum[j] + __shfl_xor(csum[j], 32, 64);
+      if (tc.half == 0) red_s[tc.wm * kTile + tc.b_row(j)] = sum;
+    }
+    __syncthreads();
+    if (threadIdx.x < kTile && t0 + threadIdx.x < n) {
+      float S = 0.f;
+#pragma unroll
+      for (int q = 0; q < kWavesA; ++q) S += red_s[q * kTile + threadIdx.x];
+      part_s[static_cast<size_t>(vt) * TC + t0 + threadIdx.x] = S;
+    }
+    // E[t][v]: 32 threads x 16 bytes cover the 512 bytes of one token row of the staged tile
+    const int col16 = threadIdx.x & 31;
+    if (v0 + col16 * 8 < Vp) {
+#pragma unroll 4
+      for (int it = 0; it < kTile / 16; ++it) {
+        const int row = it * 16 + (threadIdx.x >> 5);
+        const char* src = smem + row * kDzRowStride + col16 * 16;
+        const int flip = (col16 >> 4) << 3;        // see k_head_dz: keeps the two 8-byte reads off the same banks
+        const uint2 first = *reinterpret_cast<const uint2*>(src + flip);
+        const uint2 second = *reinterpret_cast<const uint2*>(src + (flip ^ 8));
+        const uint2 lo = flip ? second : first;
+        const uint2 hi = flip ? first : second;
+        uint4 u;
+        u.x = lo.x; u.y = lo.y; u.z = hi.x; u.w = hi.y;
+        *reinterpret_cast<uint4*>(reinterpret_cast<char*>(E) +
+                                  (static_cast<size_t>(t0 + row) * Vp + v0 + col16 * 8) * 2) = u;
+      }
+    }
+    barrier_lds_only();   // staged tile and quarter sums are free again; the stores may still fly
+  }
+}
+
+// 256 threads = 64 tokens x 4 slices of the partial sums.  Per token of the launch: S, lse, logp; the
+// backward coefficient g and the row factor a = -g / S; the element of E that carries the onehot term is
+// replaced by e_y - S.  A row whose S is not in [.., 2^60) (overflow, NaN) or whose reference is not finite
+// raises the gate and gets a = 0.
+__global__ __launch_bounds__(256) void k_fe_combine(const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
+                                                    int c0, int TC, int n_part, int head,
+                                                    const float* __restrict__ part_s, const float* __restrict__ c2,
+                                                    const float* __restrict__ zy,
+                                                    const int32_t* __restrict__ token_id, CoefArgs ca,
+                                                    float* __restrict__ logp, float* __restrict__ lse,
+                                                    float* __restrict__ scale, bf16_t* __restrict__ E, int Vp,
+                                                    int32_t* __restrict__ gate) {
+  __shared__ float ss[4][64];
+  const int n = chunk_count(cnt, c0, TC);
+  const int tx = threadIdx.x & 63, py = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + tx;
+  if (blockIdx.x * 64 >= n) return;
+  float S = 0.f;
+  if (j < n)
+    for (int p = py; p < n_part; p += 4) S += part_s[static_cast<size_t>(p) * TC + j];
+  ss[py][tx] = S;
+  __syncthreads();
+  if (py == 0 && j < n) {
+    const float St = (ss[0][tx] + ss[1][tx]) + (ss[2][tx] + ss[3][tx]);
+    const float c2v = c2[j];
+    const float l = (c2v + __log2f(St)) * kLn2;
+    const int row = idx[c0 + j];
+    const float lp = zy[j] - l;
+    logp[row] = lp;
+    lse[row] = l;
+    const bool ok = (St < kMaxRefSum) && (fabsf(c2v) < INFINITY);
+    const float g = coef_value(ca, head, row, lp);
+    scale[j] = ok ? -g / St : 0.f;
+    const float ey = fast_exp2(fmaf(zy[j], kLog2e, -c2v));
+    E[static_cast<size_t>(j) * Vp + token_id[row]] = f32_to_bf16(ey - St);
+    if (!ok) atomicOr(gate, 1);
+  }
+}
+
+// After the two-pass kernels have replaced a launch's E by softmax - onehot: a = -g.
+__global__ __launch_bounds__(256) void k_fallback_scale(const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
+                                                        int c0, int TC, int head, CoefArgs ca,
+                                                        const float* __restrict__ logp, float* __restrict__ scale,
+                                                        const int32_t* __restrict__ gate) {
+  if (*gate == 0) return;
+  const int n = chunk_count(cnt, c0, TC);
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= n) return;
+  const int row = idx[c0 + j];
+  scale[j] = -coef_value(ca, head, row, logp[row]);
+}
+
+// ------------------------------------------------------------------------------------------------
 // dHidden: A = dZ rows (tokens -> registers), B = Wt rows (h -> lanes), k = vocab
 // ------------------------------------------------------------------------------------------------
 template <typename T>
@@ -420,7 +663,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dh(const T* __restrict__ 
                                                           const int32_t* __restrict__ idx,
                                                           const int32_t* __restrict__ cnt, int c0,
                                                           T* __restrict__ d_hidden, int H, int Vp,
-                                                          int TC) {
+                                                          int TC, const float* __restrict__ scale) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int n = chunk_count(cnt, c0, TC);
   if (n <= 0) return;
@@ -450,10 +693,11 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dh(const T* __restrict__ 
         const int j = t0 + tc.a_row(i, r);
         if (j >= n) continue;
         T* out = d_hidden + static_cast<size_t>(idx[c0 + j]) * H;
+        const float sc = scale ? scale[j] : 1.f;     // row factor of the one-pass path
 #pragma unroll
         for (int jj = 0; jj < kJB; ++jj) {
           const int h = h0 + tc.b_row(jj);
-          if (h < H) out[h] = from_f32<T>(acc[i][jj][r]);
+          if (h < H) out[h] = from_f32<T>(acc[i][jj][r] * sc);
         }
       }
   }
@@ -517,7 +761,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dw(const T* __restrict__ 
 __global__ __launch_bounds__(256) void k_gather_rows(const bf16_t* __restrict__ hidden,
                                                      const int32_t* __restrict__ idx,
                                                      const int32_t* __restrict__ cnt, int c0, int TC, int H,
-                                                     bf16_t* __restrict__ hG) {
+                                                     const float* __restrict__ scale, bf16_t* __restrict__ hG) {
   const int n = chunk_count(cnt, c0, TC);
   const int n_pad = (n + kTile - 1) / kTile * kTile;
   const int chunks = H / 8;                       // 16-byte pieces per row
@@ -525,7 +769,20 @@ __global__ __launch_bounds__(256) void k_gather_rows(const bf16_t* __restrict__ 
   for (int j = blockIdx.x * rows_per_block + (threadIdx.x >> 5); j < n_pad; j += gridDim.x * rows_per_block) {
     const uint4* src = (j < n) ? reinterpret_cast<const uint4*>(hidden + static_cast<size_t>(idx[c0 + j]) * H) : nullptr;
     uint4* dst = reinterpret_cast<uint4*>(hG + static_cast<size_t>(j) * H);
-    for (int c = threadIdx.x & 31; c < chunks; c += 32) dst[c] = src ? src[c] : make_uint4(0, 0, 0, 0);
+    if (src && scale) {
+      const float sc = scale[j];
+      for (int c = threadIdx.x & 31; c < chunks; c += 32) {
+        const uint4 x = src[c];
+        const uint32_t xs[4] = {x.x, x.y, x.z, x.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          o[e] = pack_bf16x2(__uint_as_float(xs[e] << 16) * sc, __uint_as_float(xs[e] & 0xffff0000u) * sc);
+        dst[c] = make_uint4(o[0], o[1], o[2], o[3]);
+      }
+    } else {
+      for (int c = threadIdx.x & 31; c < chunks; c += 32) dst[c] = src ? src[c] : make_uint4(0, 0, 0, 0);
+    }
   }
 }
 
@@ -592,25 +849,25 @@ int gemm_grid() {
 template <typename T, bool ENT>
 int launch_head_fwd_t(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
                       const int32_t* token_id, float* part_m, float* part_s, float* part_u, float* zy,
-                      hipStream_t s) {
+                      hipStream_t s, const int32_t* gate) {
   auto k = k_head_fwd<T, ENT>;
   ATG_TRY(allow_big_lds(k));
   hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s, static_cast<const T*>(hidden),
                      static_cast<const T*>(W), ch.idx, ch.cnt, ch.c0, token_id, part_m, part_s, part_u, zy, g.H,
-                     g.V, g.TC, g.n_vtiles);
+                     g.V, g.TC, g.n_vtiles, gate);
   return AT_GRPO_OK;
 }
 
 int launch_head_fwd(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
                     const int32_t* token_id, float* part_m, float* part_s, float* part_u, float* zy,
-                    hipStream_t s) {
+                    hipStream_t s, const int32_t* gate) {
   ProfScope ps(PROF_HEAD_FWD, s);
   if (g.dtype == AT_GRPO_BF16) {
-    if (part_u) ATG_TRY((launch_head_fwd_t<bf16_t, true>(g, ch, hidden, W, token_id, part_m, part_s, part_u, zy, s)));
-    else ATG_TRY((launch_head_fwd_t<bf16_t, false>(g, ch, hidden, W, token_id, part_m, part_s, part_u, zy, s)));
+    if (part_u) ATG_TRY((launch_head_fwd_t<bf16_t, true>(g, ch, hidden, W, token_id, part_m, part_s, part_u, zy, s, gate)));
+    else ATG_TRY((launch_head_fwd_t<bf16_t, false>(g, ch, hidden, W, token_id, part_m, part_s, part_u, zy, s, gate)));
   } else {
-    if (part_u) ATG_TRY((launch_head_fwd_t<float, true>(g, ch, hidden, W, token_id, part_m, part_s, part_u, zy, s)));
-    else ATG_TRY((launch_head_fwd_t<float, false>(g, ch, hidden, W, token_id, part_m, part_s, part_u, zy, s)));
+    if (part_u) ATG_TRY((launch_head_fwd_t<float, true>(g, ch, hidden, W, token_id, part_m, part_s, part_u, zy, s, gate)));
+    else ATG_TRY((launch_head_fwd_t<float, false>(g, ch, hidden, W, token_id, part_m, part_s, part_u, zy, s, gate)));
   }
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
@@ -618,10 +875,10 @@ int launch_head_fwd(const HeadGeom& g, const HeadChunk& ch, const void* hidden, 
 
 int launch_lse_combine(const HeadGeom& g, const HeadChunk& ch, const float* part_m, const float* part_s,
                        const float* part_u, const float* zy, float* logp, float* lse, float* entropy,
-                       hipStream_t s) {
+                       hipStream_t s, const int32_t* gate) {
   ProfScope ps(PROF_LSE_COMBINE, s);
   hipLaunchKernelGGL(k_lse_combine, dim3(g.TC / 64), dim3(256), 0, s, ch.idx, ch.cnt, ch.c0, g.TC,
-                     g.n_vtiles, part_m, part_s, part_u, zy, logp, lse, part_u ? entropy : nullptr);
+                     g.n_vtiles, part_m, part_s, part_u, zy, logp, lse, part_u ? entropy : nullptr, gate);
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }
@@ -642,12 +899,12 @@ int launch_transpose_w(const HeadGeom& g, const void* W, void* Wt, hipStream_t s
 }
 
 int launch_gather_transpose_hidden(const HeadGeom& g, const HeadChunk& ch, const void* hidden, void* hT,
-                                   hipStream_t s) {
+                                   hipStream_t s, const float* scale) {
   ProfScope ps(PROF_TRANSPOSE, s);
   if (g.dtype == AT_GRPO_BF16) {
     // bf16: plain row gather (the token contraction reads it k-major)
     hipLaunchKernelGGL(k_gather_rows, dim3(2048), dim3(256), 0, s, static_cast<const bf16_t*>(hidden), ch.idx,
-                       ch.cnt, ch.c0, g.TC, g.H, static_cast<bf16_t*>(hT));
+                       ch.cnt, ch.c0, g.TC, g.H, scale, static_cast<bf16_t*>(hT));
   } else {
     dim3 grid(static_cast<unsigned>(g.TC / 64), static_cast<unsigned>(ceil_div(g.H, 64)));
     hipLaunchKernelGGL(k_transpose<float>, grid, dim3(256), 0, s, static_cast<const float*>(hidden),
@@ -660,7 +917,7 @@ int launch_gather_transpose_hidden(const HeadGeom& g, const HeadChunk& ch, const
 
 int launch_head_dz(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
                    const int32_t* token_id, const float* lse, const float* coef, void* dZ, void* dZt,
-                   hipStream_t s) {
+                   hipStream_t s, const int32_t* gate) {
   ProfScope ps(PROF_HEAD_DZ, s);
   if (g.dtype == AT_GRPO_BF16) {
     auto k = k_head_dz<bf16_t>;
@@ -669,34 +926,76 @@ int launch_head_dz(const HeadGeom& g, const HeadChunk& ch, const void* hidden, c
     hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), lds, s,
                        static_cast<const bf16_t*>(hidden), static_cast<const bf16_t*>(W), ch.idx, ch.cnt,
                        ch.c0, token_id, lse, coef, static_cast<bf16_t*>(dZ), static_cast<bf16_t*>(dZt),
-                       g.H, g.V, g.Vp, g.TC, g.n_vtiles);
+                       g.H, g.V, g.Vp, g.TC, g.n_vtiles, gate);
   } else {
     auto k = k_head_dz<float>;
     ATG_TRY(allow_big_lds(k));
     hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
                        static_cast<const float*>(hidden), static_cast<const float*>(W), ch.idx, ch.cnt,
                        ch.c0, token_id, lse, coef, static_cast<float*>(dZ), static_cast<float*>(dZt), g.H,
-                       g.V, g.Vp, g.TC, g.n_vtiles);
+                       g.V, g.Vp, g.TC, g.n_vtiles, gate);
   }
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }
 
+int launch_ref_logit(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
+                     const int32_t* token_id, float* c2, hipStream_t s) {
+  ProfScope ps(PROF_LSE_COMBINE, s);
+  if (g.dtype != AT_GRPO_BF16) return AT_GRPO_EUNSUPPORTED;
+  hipLaunchKernelGGL(k_ref_logit, dim3(g.TC / 4), dim3(256), 0, s, static_cast<const bf16_t*>(hidden),
+                     static_cast<const bf16_t*>(W), ch.idx, ch.cnt, ch.c0, g.TC, token_id, g.H, c2);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_head_fe(const HeadGeom& g, const HeadChunk& ch, const void* hidden, const void* W,
+                   const int32_t* token_id, const float* c2, void* E, float* part_s, float* zy, hipStream_t s) {
+  ProfScope ps(PROF_HEAD_FE, s);
+  if (g.dtype != AT_GRPO_BF16) return AT_GRPO_EUNSUPPORTED;
+  auto k = k_head_fe;
+  ATG_TRY(allow_big_lds(k, kFeLdsBytes));
+  hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kFeLdsBytes, s, static_cast<const bf16_t*>(hidden),
+                     static_cast<const bf16_t*>(W), ch.idx, ch.cnt, ch.c0, token_id, c2, static_cast<bf16_t*>(E),
+                     part_s, zy, g.H, g.V, g.Vp, g.TC, g.n_vtiles);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_fe_combine(const HeadGeom& g, const HeadChunk& ch, int head, const float* part_s, const float* c2,
+                      const float* zy, const int32_t* token_id, const CoefArgs& ca, float* logp, float* lse,
+                      float* scale, void* E, int32_t* gate, hipStream_t s) {
+  ProfScope ps(PROF_LSE_COMBINE, s);
+  hipLaunchKernelGGL(k_fe_combine, dim3(g.TC / 64), dim3(256), 0, s, ch.idx, ch.cnt, ch.c0, g.TC, g.n_vtiles,
+                     head, part_s, c2, zy, token_id, ca, logp, lse, scale, static_cast<bf16_t*>(E), g.Vp, gate);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_fallback_scale(const HeadGeom& g, const HeadChunk& ch, int head, const CoefArgs& ca, const float* logp,
+                          float* scale, const int32_t* gate, hipStream_t s) {
+  ProfScope ps(PROF_COEF, s);
+  hipLaunchKernelGGL(k_fallback_scale, dim3(g.TC / 256), dim3(256), 0, s, ch.idx, ch.cnt, ch.c0, g.TC, head, ca,
+                     logp, scale, gate);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
 int launch_head_dh(const HeadGeom& g, const HeadChunk& ch, const void* dZ, const void* Wt, void* d_hidden,
-                   hipStream_t s) {
+                   hipStream_t s, const float* scale) {
   ProfScope ps(PROF_HEAD_DH, s);
   if (g.dtype == AT_GRPO_BF16) {
     auto k = k_head_dh<bf16_t>;
     ATG_TRY(allow_big_lds(k));
     hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
                        static_cast<const bf16_t*>(dZ), static_cast<const bf16_t*>(Wt), ch.idx, ch.cnt, ch.c0,
-                       static_cast<bf16_t*>(d_hidden), g.H, g.Vp, g.TC);
+                       static_cast<bf16_t*>(d_hidden), g.H, g.Vp, g.TC, scale);
   } else {
     auto k = k_head_dh<float>;
     ATG_TRY(allow_big_lds(k));
     hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
                        static_cast<const float*>(dZ), static_cast<const float*>(Wt), ch.idx, ch.cnt, ch.c0,
-                       static_cast<float*>(d_hidden), g.H, g.Vp, g.TC);
+                       static_cast<float*>(d_hidden), g.H, g.Vp, g.TC, scale);
   }
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;

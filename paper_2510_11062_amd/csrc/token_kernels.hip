@@ -157,23 +157,6 @@ __global__ __launch_bounds__(256) void k_resp_cnt(TokenLayout L, const int32_t* 
   }
 }
 
-struct ClipConst {
-  float lo, hi;          // log-space thresholds
-  float one_minus, one_plus;
-};
-
-// Per-token pieces of Eq. (2).  Returns l_t; sets *bits and *ratio.
-__device__ __forceinline__ float surrogate_term(float logp, float old_logp, float A, const ClipConst& c,
-                                                int* bits, float* ratio) {
-  const float d = logp - old_logp;
-  const float r = expf(d);
-  const bool low = d < c.lo, high = d > c.hi;
-  const bool zero = (high && A > 0.f) || (low && A < 0.f);
-  *bits = (low ? AT_GRPO_CLIP_LOW : 0) | (high ? AT_GRPO_CLIP_HIGH : 0) | (zero ? AT_GRPO_CLIP_ZERO_GRAD : 0);
-  *ratio = r;
-  return zero ? (high ? c.one_plus : c.one_minus) * A : r * A;
-}
-
 // LPR lanes per response (64, 32 or 16, chosen from the mean response length): every row of the
 // response is read once (logp, old_logp, mask, and token_id when given) in 4-row vectors, its clip
 // flags are written, and the response's sum of surrogate terms and its count of participating rows
@@ -443,38 +426,34 @@ __global__ __launch_bounds__(1024) void k_diag_final(int n_resp, DiagPartials P,
   }
 }
 
-__global__ __launch_bounds__(256) void k_coef(int64_t n_tok, int32_t* __restrict__ flag,
-                                              const int32_t* __restrict__ resp_of_tok,
-                                              const int32_t* __restrict__ resp_len,
-                                              const int32_t* __restrict__ cnt,
-                                              const int32_t* __restrict__ resp_cnt,
-                                              const float* __restrict__ logp,
-                                              const float* __restrict__ old_logp,
-                                              const float* __restrict__ adv, ClipConst cc, int agg,
-                                              const float* __restrict__ grad_loss,
-                                              float* __restrict__ coef) {
+__global__ __launch_bounds__(256) void k_coef(int64_t n_tok, int32_t* __restrict__ flag, CoefArgs ca,
+                                              const float* __restrict__ logp, float* __restrict__ coef) {
   const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   if (t >= n_tok) return;
   const int f = flag[t];
   float g = 0.f;
   if (f >= 0) {
-    const int r = resp_of_tok[t];
-    const float A = adv[r];
-    int bits;
-    float ratio;
-    surrogate_term(logp[t], old_logp[t], A, cc, &bits, &ratio);
-    float w;
-    if (agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN)
-      w = 1.f / (static_cast<float>(resp_cnt[f]) * static_cast<float>(resp_len[r]));
-    else
-      w = 1.f / static_cast<float>(cnt[f]);
-    if (!(bits & AT_GRPO_CLIP_ZERO_GRAD)) g = -w * A * ratio * (grad_loss ? grad_loss[f] : 1.f);
+    g = coef_value(ca, f, t, logp[t]);
     if (g == 0.f) {
       g = 0.f;          // also folds -0
       flag[t] = -1;
     }
   }
   coef[t] = g;
+}
+
+__global__ __launch_bounds__(256) void k_split_by_advantage(int64_t n_tok, const int32_t* __restrict__ flag,
+                                                            const int32_t* __restrict__ resp_of_tok,
+                                                            const float* __restrict__ adv,
+                                                            int32_t* __restrict__ flag_b,
+                                                            int32_t* __restrict__ flag_f) {
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (t >= n_tok) return;
+  const int f = flag[t];
+  bool grad = false;
+  if (f >= 0) grad = adv[resp_of_tok[t]] != 0.f;   // NaN counts as non-zero and propagates
+  flag_b[t] = (f >= 0 && grad) ? f : -1;
+  flag_f[t] = (f >= 0 && !grad) ? f : -1;
 }
 
 __global__ __launch_bounds__(256) void k_zero_nonparticipating(int64_t n_tok,
@@ -487,15 +466,6 @@ __global__ __launch_bounds__(256) void k_zero_nonparticipating(int64_t n_tok,
     logp[t] = 0.f;
     if (lse) lse[t] = 0.f;
   }
-}
-
-ClipConst make_clip(float eps_low, float eps_high) {
-  ClipConst c;
-  c.lo = static_cast<float>(log1p(-static_cast<double>(eps_low)));
-  c.hi = static_cast<float>(log1p(static_cast<double>(eps_high)));
-  c.one_minus = 1.f - eps_low;
-  c.one_plus = 1.f + eps_high;
-  return c;
 }
 
 unsigned grid_for(int64_t n, int per_block, int64_t cap = 1 << 20) {
@@ -613,14 +583,37 @@ int launch_diagnostics(const TokenLayout& L, const float* logp, const float* old
   return AT_GRPO_OK;
 }
 
+CoefArgs make_coef_args(const TokenScratch& S, const float* old_logp, const float* adv, float eps_low,
+                        float eps_high, int agg, const float* grad_loss) {
+  CoefArgs ca;
+  ca.resp_of_tok = S.resp_of_tok;
+  ca.resp_len = S.resp_len;
+  ca.cnt = S.cnt;
+  ca.resp_cnt = S.resp_cnt;
+  ca.old_logp = old_logp;
+  ca.adv = adv;
+  ca.grad_loss = grad_loss;
+  ca.cc = make_clip(eps_low, eps_high);
+  ca.agg = agg;
+  return ca;
+}
+
 int launch_coef(const TokenLayout& L, const TokenScratch& S, const float* logp, const float* old_logp,
                 const float* adv, float eps_low, float eps_high, int agg, const float* grad_loss,
                 float* coef, hipStream_t s) {
   ProfScope ps(PROF_COEF, s);
-  const ClipConst cc = make_clip(eps_low, eps_high);
-  hipLaunchKernelGGL(k_coef, dim3(static_cast<unsigned>(S.n_blk256)), dim3(256), 0, s, L.n_tok, S.flag,
-                     S.resp_of_tok, S.resp_len, S.cnt, S.resp_cnt, logp, old_logp, adv, cc, agg, grad_loss,
+  const CoefArgs ca = make_coef_args(S, old_logp, adv, eps_low, eps_high, agg, grad_loss);
+  hipLaunchKernelGGL(k_coef, dim3(static_cast<unsigned>(S.n_blk256)), dim3(256), 0, s, L.n_tok, S.flag, ca, logp,
                      coef);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
+int launch_split_by_advantage(const TokenLayout& L, const TokenScratch& S, const float* adv, int32_t* flag_b,
+                              int32_t* flag_f, hipStream_t s) {
+  ProfScope ps(PROF_PREP, s);
+  hipLaunchKernelGGL(k_split_by_advantage, dim3(static_cast<unsigned>(S.n_blk256)), dim3(256), 0, s, L.n_tok,
+                     S.flag, S.resp_of_tok, adv, flag_b, flag_f);
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }

@@ -3,6 +3,8 @@
 // the backward coefficient.
 #pragma once
 
+#include <math.h>
+
 #include "common.hpp"
 
 namespace atg {
@@ -35,6 +37,67 @@ struct TokenScratch {
   int64_t n_blk256;      // ceil(n_tok / 256)
 };
 
+// ---- Eq. (2) per token ---------------------------------------------------------------------------
+struct ClipConst {
+  float lo, hi;          // log-space thresholds
+  float one_minus, one_plus;
+};
+
+inline ClipConst make_clip(float eps_low, float eps_high) {
+  ClipConst c;
+  c.lo = static_cast<float>(log1p(-static_cast<double>(eps_low)));
+  c.hi = static_cast<float>(log1p(static_cast<double>(eps_high)));
+  c.one_minus = 1.f - eps_low;
+  c.one_plus = 1.f + eps_high;
+  return c;
+}
+
+// What the backward coefficient of one row needs besides its log-probability.
+struct CoefArgs {
+  const int32_t* resp_of_tok;   // [n_tok]
+  const int32_t* resp_len;      // [n_resp] participating rows per response (sequence-mean aggregation)
+  const int32_t* cnt;           // [kMaxHeads] participating rows per head (token-mean aggregation)
+  const int32_t* resp_cnt;      // [kMaxHeads] responses with a participating row, per head
+  const float* old_logp;
+  const float* adv;
+  const float* grad_loss;       // [n_heads] or null (= 1)
+  ClipConst cc;
+  int agg;
+};
+
+CoefArgs make_coef_args(const TokenScratch& S, const float* old_logp, const float* adv, float eps_low,
+                        float eps_high, int agg, const float* grad_loss);
+
+#ifdef __HIPCC__
+// Per-token pieces of Eq. (2).  Returns l_t; sets *bits and *ratio.
+__device__ __forceinline__ float surrogate_term(float logp, float old_logp, float A, const ClipConst& c,
+                                                int* bits, float* ratio) {
+  const float d = logp - old_logp;
+  const float r = expf(d);
+  const bool low = d < c.lo, high = d > c.hi;
+  const bool zero = (high && A > 0.f) || (low && A < 0.f);
+  *bits = (low ? AT_GRPO_CLIP_LOW : 0) | (high ? AT_GRPO_CLIP_HIGH : 0) | (zero ? AT_GRPO_CLIP_ZERO_GRAD : 0);
+  *ratio = r;
+  return zero ? (high ? c.one_plus : c.one_minus) * A : r * A;
+}
+
+// g_t = d loss / d logp_t of a participating row t of head `head` (0 on the clipped branch).
+__device__ __forceinline__ float coef_value(const CoefArgs& a, int head, int64_t t, float logp) {
+  const int r = a.resp_of_tok[t];
+  const float A = a.adv[r];
+  int bits;
+  float ratio;
+  surrogate_term(logp, a.old_logp[t], A, a.cc, &bits, &ratio);
+  float w;
+  if (a.agg == AT_GRPO_AGG_SEQ_MEAN_TOKEN_MEAN)
+    w = 1.f / (static_cast<float>(a.resp_cnt[head]) * static_cast<float>(a.resp_len[r]));
+  else
+    w = 1.f / static_cast<float>(a.cnt[head]);
+  if (bits & AT_GRPO_CLIP_ZERO_GRAD) return 0.f;
+  return -w * A * ratio * (a.grad_loss ? a.grad_loss[head] : 1.f);
+}
+#endif  // __HIPCC__
+
 int launch_fill_i32(int32_t* p, int64_t n, int32_t value, hipStream_t s);
 int launch_fill_bytes16(void* p, int64_t n_bytes, hipStream_t s);   // zero fill, n_bytes % 16 == 0
 
@@ -65,6 +128,11 @@ int launch_diagnostics(const TokenLayout& L, const float* logp, const float* old
 int launch_coef(const TokenLayout& L, const TokenScratch& S, const float* logp, const float* old_logp,
                 const float* adv, float eps_low, float eps_high, int agg, const float* grad_loss,
                 float* coef, hipStream_t s);
+
+// Splits the participating rows by their response's advantage: flag_b = flag where adv != 0 (these rows can
+// carry gradient), flag_f = flag where adv == 0 (log-probability only); -1 elsewhere in both.
+int launch_split_by_advantage(const TokenLayout& L, const TokenScratch& S, const float* adv, int32_t* flag_b,
+                              int32_t* flag_f, hipStream_t s);
 
 // logp = lse = 0 on rows with flag < 0.
 int launch_zero_nonparticipating(const TokenLayout& L, const TokenScratch& S, float* logp, float* lse,

@@ -1,0 +1,180 @@
+"""Parity of at_grpo_policy_loss_fwd_bwd (forward and backward from one pass over the logits) against
+the CPU oracle, with the tolerances of tests/test_gpu_parity.py: log-probs 1e-2 absolute (bf16) / 1e-4
+relative (fp32), loss 2e-2 / 1e-4 relative, gradients row by row and element by element at 2e-2 / 1e-4,
+integer outputs bit-exact.  The call must also agree with the two-call sequence it stands for.
+"""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import at_grpo_oracle as orc
+from paper_2510_11062_amd import api, synth
+from tests import helpers
+from tests.gpu_case import DeviceCase, host
+from tests.test_gpu_parity import assert_logp_close, compare_clip_masks, mini_cfg, say, tolerances
+
+
+def near_threshold(ref, old_logp, cfg, err):
+    lo32, hi32 = orc.clip_thresholds(cfg.eps_clip, cfg.eps_clip)
+    d = ref["logp"].astype(np.float32) - old_logp
+    w = max(10 * err, 1e-6)
+    return (np.abs(d - lo32) <= w) | (np.abs(d - hi32) <= w)
+
+
+def check_step_against_oracle(out, ref, c, cfg, tol, tag, grad_check=True):
+    """Every output of the one-pass call against the oracle's forward + backward."""
+    err = assert_logp_close(host(out["logp"]), ref["logp"], tol, f"{tag}.logp")
+    assert_logp_close(host(out["lse"]), ref["lse"], tol, f"{tag}.lse")
+    assert np.array_equal(host(out["n_valid"]), ref["n_valid"])
+    loss = host(out["loss"]).astype(np.float64)
+    assert np.all(np.abs(loss - ref["loss"]) <= tol["loss_rel"] * np.abs(ref["loss"]) + 1e-5), (loss, ref["loss"])
+    n_near = compare_clip_masks(host(out["clip_mask"]), ref, c.old_logp, cfg, max(10 * err, 1e-6))
+    off = ref["w"] == 0
+    assert np.all(host(out["logp"])[off] == 0) and np.all(host(out["lse"])[off] == 0)
+    assert np.all(host(out["clip_mask"])[off] == 0)
+    say(f"[{tag}] loss {loss} vs {ref['loss']}; logp err {err:.2e}; {n_near} tokens next to a threshold")
+    if not grad_check:
+        return err
+    near = near_threshold(ref, c.old_logp, cfg, err)
+    dH = host(out["d_hidden"]).astype(np.float64)
+    assert np.all(dH[(ref["g"] == 0) & ~near] == 0), "rows without gradient must be exactly zero"
+    r = helpers.assert_grad_close(dH[~near], ref["d_hidden"][~near], tol["grad_rel"], f"{tag}.d_hidden")
+    say(f"[{tag}] d_hidden worst row {r[0]:.3e}, worst element {r[1]:.3e}, Frobenius {r[2]:.3e}")
+    if not near.any():
+        for k in range(cfg.n_heads):
+            r = helpers.assert_grad_close(host(out["dW"][k]), ref["dW"][k], tol["grad_rel"], f"{tag}.dW[{k}]")
+            say(f"[{tag}] dW[{k}] worst row {r[0]:.3e}, worst element {r[1]:.3e}, Frobenius {r[2]:.3e}")
+    return err
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("agg", ["token_mean", "seq_mean_token_mean"])
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_one_pass_step_matches_oracle(gpu_device, name, agg):
+    cfg = mini_cfg(name)
+    if agg == "seq_mean_token_mean" and name in ("C2", "C4"):
+        pytest.skip("the second aggregation is covered on C1, C3 and C5")
+    tol = tolerances(cfg)
+    say(f"[one-pass] building {cfg.name}: H={cfg.H} V={cfg.V} heads={cfg.n_heads} agg={agg}")
+    c = helpers.build_case(cfg, device=gpu_device)
+    if name == "C5":   # more drift so that the clipped branches carry real weight
+        c.old_logp = (c.old_logp + c.noise).astype(np.float32)
+    grad_loss = None if cfg.n_heads == 1 else np.linspace(1.0, 0.5, cfg.n_heads)
+    ref = helpers.oracle_bwd(c, agg=agg, grad_loss=grad_loss)
+    say(f"[one-pass] {int((ref['g'] != 0).sum())} of {c.st.n_valid} response tokens carry gradient; "
+        f"{int(((ref['w'] != 0) & (c.adv[c.resp_of_tok] == 0)).sum())} belong to zero-advantage responses")
+    dc = DeviceCase(c, gpu_device)
+    gl = None if grad_loss is None else torch.from_numpy(grad_loss.astype(np.float32)).to(gpu_device)
+    out = api.at_grpo_policy_loss_fwd_bwd(dc.batch(), dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip, agg=agg,
+                                          grad_loss=gl)
+    torch.cuda.synchronize()
+    assert api.error_word(out["workspace"]) == 0
+    check_step_against_oracle(out, ref, c, cfg, tol, "one-pass")
+
+    say("[one-pass] against the two-call sequence")
+    fwd = api.at_grpo_policy_loss_fwd(dc.batch(), dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip, agg=agg)
+    bwd = api.at_grpo_policy_loss_bwd(dc.batch(), dc.old_logp, dc.adv, fwd["logp"], fwd["lse"], cfg.eps_clip,
+                                      cfg.eps_clip, agg=agg, grad_loss=gl)
+    torch.cuda.synchronize()
+    assert torch.equal(out["n_valid"], fwd["n_valid"])
+    assert float((out["logp"] - fwd["logp"]).abs().max()) <= (1e-2 if cfg.dtype == "bf16" else 1e-5)
+    if cfg.dtype == "f32":
+        assert torch.equal(out["d_hidden"], bwd["d_hidden"]) and torch.equal(out["dW"][0], bwd["dW"][0])
+
+    say("[one-pass] accumulate_dW adds onto an existing gradient")
+    gen = torch.Generator(device=gpu_device)
+    gen.manual_seed(11)
+    base = [torch.randn(g.shape, generator=gen, device=gpu_device) * g.abs().mean() for g in out["dW"]]
+    before = [b.clone() for b in base]
+    acc = api.at_grpo_policy_loss_fwd_bwd(dc.batch(), dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip, agg=agg,
+                                          grad_loss=gl, dW=base, accumulate_dW=True)
+    torch.cuda.synchronize()
+    for k in range(cfg.n_heads):
+        assert torch.allclose(acc["dW"][k], before[k] + out["dW"][k], rtol=0,
+                              atol=1e-6 * float(out["dW"][k].abs().max()))
+    assert torch.equal(acc["d_hidden"], out["d_hidden"])
+    assert torch.equal(acc["logp"], out["logp"])
+
+
+@pytest.mark.gpu
+def test_one_pass_across_several_super_chunks(gpu_device):
+    """More than two super-chunks of gradient rows per head plus a ragged last one, a ragged vocabulary
+    tile (V = 1001) and two heads: dW accumulates across launches inside the call, and every output is
+    compared with the fp64 oracle element by element.  A second call adds onto a random pre-filled dW."""
+    cfg = replace(synth.CONFIGS["C3"], name="one-pass-chunks", dtype="bf16", H=128, V=1001, n_heads=2, E=24, N=2,
+                  T=2, K=8, len_lo=180, len_hi=280, reward_kind="uniform", forced_equal_groups=2,
+                  seed=synth.BASE_SEED + 901)
+    tol = tolerances(cfg)
+    c = helpers.build_case(cfg, device=gpu_device)
+    grad_loss = np.array([1.0, 0.5])
+    say(f"[one-pass chunks] oracle on {c.st.n_tok} rows")
+    ref = helpers.oracle_bwd(c, grad_loss=grad_loss)
+    live = c.adv[c.resp_of_tok] != 0
+    per_head = [int((live & (ref["w"] != 0) & (c.head_of_tok == k)).sum()) for k in range(2)]
+    say(f"[one-pass chunks] rows of non-zero advantage per head: {per_head}")
+    assert min(per_head) > 2 * 32768 and all(n % 32768 != 0 for n in per_head)
+    dc = DeviceCase(c, gpu_device)
+    gl = torch.from_numpy(grad_loss.astype(np.float32)).to(gpu_device)
+    out = api.at_grpo_policy_loss_fwd_bwd(dc.batch(), dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip, grad_loss=gl)
+    torch.cuda.synchronize()
+    assert api.error_word(out["workspace"]) == 0
+    err = check_step_against_oracle(out, ref, c, cfg, tol, "one-pass chunks")
+    near = near_threshold(ref, c.old_logp, cfg, err)
+    say(f"[one-pass chunks] {int(near.sum())} tokens next to a threshold")
+    gen = torch.Generator(device=gpu_device)
+    gen.manual_seed(13)
+    base = [torch.randn(g.shape, generator=gen, device=gpu_device) * g.abs().mean() for g in out["dW"]]
+    before = [b.clone() for b in base]
+    acc = api.at_grpo_policy_loss_fwd_bwd(dc.batch(), dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip, grad_loss=gl,
+                                          dW=base, accumulate_dW=True)
+    torch.cuda.synchronize()
+    for k in range(2):
+        added = host(acc["dW"][k]).astype(np.float64) - host(before[k]).astype(np.float64)
+        if not near.any():
+            helpers.assert_grad_close(added, ref["dW"][k], max(tol["grad_rel"], 1e-3), f"accumulated dW[{k}]")
+        assert torch.allclose(acc["dW"][k], before[k] + out["dW"][k], rtol=0,
+                              atol=1e-6 * float(out["dW"][k].abs().max()))
+
+
+@pytest.mark.gpu
+def test_one_pass_falls_back_when_the_exponent_range_is_exceeded(gpu_device):
+    """Hidden states scaled up until, for some rows, the largest logit exceeds the sampled token's by more
+    than 88 (exp overflows in fp32 relative to that reference; the oracle's logits show it): the call must
+    redo those launches with the two-pass kernels and still match the oracle, on rows with and without the
+    overflow alike.  Token ids are drawn uniformly here so that unlikely tokens occur."""
+    cfg = replace(synth.CONFIGS["C2"], name="one-pass-range", H=128, V=1500, E=2, N=2, T=2, K=4, len_lo=20, len_hi=60,
+                  padded=False, reward_kind="uniform", forced_equal_groups=0, seed=synth.BASE_SEED + 902)
+    tol = tolerances(cfg)
+    c = helpers.build_case(cfg, device=gpu_device)
+    # scale the hidden states (exactly representable factor) and resample tokens uniformly
+    scale = 64.0
+    c.hidden_t = (c.hidden_t.float() * scale).to(c.hidden_t.dtype)
+    c.hidden = helpers.to_np(c.hidden_t)
+    rng = np.random.default_rng(cfg.seed)
+    c.token_id = rng.integers(0, cfg.V, size=c.st.n_tok).astype(np.int32)
+    z = orc.head_logits(c.hidden, c.W[0])
+    gap = z.max(axis=1) - z[np.arange(c.st.n_tok), c.token_id]
+    lse = z.max(axis=1) + np.log(np.exp(z - z.max(axis=1, keepdims=True)).sum(axis=1))
+    logp = z[np.arange(c.st.n_tok), c.token_id] - lse
+    c.old_logp = (logp + 0.05 * c.noise).astype(np.float32)
+    say(f"[one-pass range] largest logit minus target logit: max {gap.max():.1f}, rows above 88: {int((gap > 88).sum())}, "
+        f"rows below 60: {int((gap < 60).sum())}")
+    assert (gap > 95).any() and (gap < 60).any()
+    ref = helpers.oracle_bwd(c)
+    dc = DeviceCase(c, gpu_device)
+    out = api.at_grpo_policy_loss_fwd_bwd(dc.batch(), dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip)
+    torch.cuda.synchronize()
+    assert api.error_word(out["workspace"]) == 0
+    assert all(torch.isfinite(out[k].float()).all() for k in ("logp", "lse", "loss", "d_hidden"))
+    # log-probs of this case are large (tens to hundreds): compare relative to their size
+    lp, lr = host(out["logp"]).astype(np.float64), ref["logp"]
+    assert np.all(np.abs(lp - lr) <= 1e-2 + 1e-5 * np.abs(lr)), float(np.abs(lp - lr).max())
+    near = near_threshold(ref, c.old_logp, cfg, float(np.abs(lp - lr).max()))
+    dH = host(out["d_hidden"]).astype(np.float64)
+    helpers.assert_grad_close(dH[~near], ref["d_hidden"][~near], tol["grad_rel"], "d_hidden")
+    if not near.any():
+        helpers.assert_grad_close(host(out["dW"][0]), ref["dW"][0], tol["grad_rel"], "dW")
+    else:
+        say(f"[one-pass range] {int(near.sum())} tokens next to a threshold: dW not compared")
