@@ -8,6 +8,8 @@ One JSON line per case: variant, shape, TFLOP/s, shader clock.  Shapes (bf16, fp
   dHidden        tokens x H x vocabulary                         16384 x 2048 x 151936   (long k)
   dW             vocabulary x H x tokens of a super-chunk, both operands k-major  151808 x 2048 x 32768
   a square case  8192^3
+nt4 / km4 are the same loops with 4 wavefronts of 128 x 128 per workgroup instead of 8 of 64 x 128: the
+library uses them where k is long (dHidden, dW) and the 8-wavefront form where k = H (forward).
 The probe (csrc/gemm_probe.hip, built by build.py) runs the library's own loop without any epilogue;
 torch.mm is timed with the output written.  A measurement aid: nothing in the library calls this.
 """
@@ -26,8 +28,11 @@ PROBE = os.path.join(PKG, "gemm_probe")
 
 SHAPES = [
     ("forward / dZ (short k)", "nt", 151808, 16384, 2048),
+    ("forward / dZ (short k), 4 wavefronts", "nt4", 151808, 16384, 2048),
     ("dHidden (long k)", "nt", 16384, 2048, 151936),
+    ("dHidden (long k), 4 wavefronts", "nt4", 16384, 2048, 151936),
     ("dW (k-major operands)", "km", 151808, 2048, 32768),
+    ("dW (k-major operands), 4 wavefronts", "km4", 151808, 2048, 32768),
     ("square", "nt", 8192, 8192, 8192),
     ("microbenchmark shape", "nt", 37888, 32768, 1984),
     ("microbenchmark shape, two workgroups per CU (rejected layout)", "wg2", 37888, 32768, 1952),
@@ -36,7 +41,7 @@ SHAPES = [
 
 def vendor(label, variant, M, N, K, iters=4):
     dev = torch.device("cuda:0")
-    if variant == "km":
+    if variant.startswith("km"):
         a = torch.randn(K, M, device=dev, dtype=torch.bfloat16)
         b = torch.randn(K, N, device=dev, dtype=torch.bfloat16)
         fn = lambda: a.T @ b
@@ -75,7 +80,7 @@ def main():
         sys.exit(2)
     for label, variant, M, N, K in SHAPES:
         print(json.dumps(probe(label, variant, M, N, K)), flush=True)
-        if variant != "wg2":
+        if variant in ("nt", "km"):     # one vendor line per shape
             print(json.dumps(vendor(label, variant, M, N, K)), flush=True)
 
 

@@ -38,16 +38,43 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
 constexpr int kTile = 256;                       // rows of each operand per tile
 constexpr int kStepBytes = 128;                  // bytes of k per row per step
-constexpr int kWavesA = 4, kWavesB = 2;
-constexpr int kGemmThreads = kWavesA * kWavesB * 64;
-constexpr int kIB = kTile / kWavesA / 32;        // 2 accumulator block rows per wavefront
-constexpr int kJB = kTile / kWavesB / 32;        // 4 accumulator block columns per wavefront
 constexpr int kLdsOperand = kTile * kStepBytes;  // 32 KiB
 constexpr int kLdOperandOffset = kLdsOperand;    // B follows A inside a stage
 constexpr int kLdsStage = 2 * kLdsOperand;       // A then B
 constexpr int kLdsBytes = 2 * kLdsStage;         // two stages: 128 KiB
-constexpr int kRowsPerWave = kTile / (kWavesA * kWavesB);   // operand rows each wavefront loads
-constexpr int kLoadsPerWave = kRowsPerWave / 8;             // direct-load instructions per operand
+
+// How the wavefronts of a workgroup share the 256 x 256 tile: WA x WB wavefronts, each owning a
+// (256 / WA) x (256 / WB) sub-tile.  Two layouts are used:
+//   WaveGrid<4, 2>  8 wavefronts, two per SIMD, 64 x 128 each (128 accumulator registers): the second
+//                   wavefront of a SIMD covers part of the other's per-tile prologue and epilogue, which
+//                   matters when the k loop is short (forward kernels: k = H);
+//   WaveGrid<2, 2>  4 wavefronts, one per SIMD, 128 x 128 each (256 accumulator registers): a third fewer
+//                   LDS fragment reads per MFMA and half as many wavefronts at each barrier; faster once
+//                   the k loop is long and the epilogue light (dHidden: k = V); slower on short loops, and
+//                   slower for dW, whose epilogue adds 256 fp32 values per lane to memory.
+template <int WA, int WB>
+struct WaveGrid {
+  static constexpr int kWavesA = WA, kWavesB = WB;
+  static constexpr int kThreads = WA * WB * 64;
+  static constexpr int kIB = kTile / WA / 32;              // accumulator block rows per wavefront
+  static constexpr int kJB = kTile / WB / 32;              // accumulator block columns per wavefront
+  static constexpr int kRowsPerWave = kTile / (WA * WB);   // operand rows each wavefront loads
+  static constexpr int kLoadsPerWave = kRowsPerWave / 8;   // direct-load instructions per operand
+  static constexpr int kMmPerSub = kIB * kJB;              // MFMA groups per 16-wide sub-step
+  static constexpr int kRdPerSub = kIB + kJB;              // fragment reads per sub-step
+  static constexpr int kRdEvery = kMmPerSub / kRdPerSub;   // a fragment read follows every kRdEvery-th MFMA
+  static constexpr int kLdPerStep = 2 * kLoadsPerWave;     // direct loads per k-step
+  static constexpr int kLdSub3 = kLdPerStep * 3 / 8;       // requested in sub-step 3 of the step two ahead
+  static constexpr int kLdSub0 = kLdPerStep * 3 / 8;       // ... in sub-step 0 of the step before
+  static constexpr int kLdSub1 = kLdPerStep - kLdSub3 - kLdSub0;
+};
+using G8 = WaveGrid<4, 2>;
+using G4 = WaveGrid<2, 2>;
+
+// the 8-wavefront layout under its short names (forward, exponentials, dZ)
+constexpr int kWavesA = G8::kWavesA, kWavesB = G8::kWavesB;
+constexpr int kGemmThreads = G8::kThreads;
+constexpr int kIB = G8::kIB, kJB = G8::kJB;
 
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
@@ -74,22 +101,24 @@ struct Mma<float> {
   }
 };
 
-struct TileCoord {
+template <typename G>
+struct TileCoordT {
   int lane, wm, wn, half;
-  __device__ __forceinline__ TileCoord() {
+  __device__ __forceinline__ TileCoordT() {
     lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    wm = wave / kWavesB;
-    wn = wave % kWavesB;
+    wm = wave / G::kWavesB;
+    wn = wave % G::kWavesB;
     half = lane >> 5;
   }
   // A row (inside the tile) of accumulator register r of block row i
   __device__ __forceinline__ int a_row(int i, int r) const {
-    return wm * (kTile / kWavesA) + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+    return wm * (kTile / G::kWavesA) + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
   }
   // B row (inside the tile) of block column j
-  __device__ __forceinline__ int b_row(int j) const { return wn * (kTile / kWavesB) + j * 32 + (lane & 31); }
+  __device__ __forceinline__ int b_row(int j) const { return wn * (kTile / G::kWavesB) + j * 32 + (lane & 31); }
 };
+using TileCoord = TileCoordT<G8>;
 
 // 16 bytes per lane, global -> LDS at (wave-uniform) lds_addr + lane * 16.
 __device__ __forceinline__ void direct_load16(const char* g, uint32_t lds_addr_uniform) {
@@ -117,23 +146,17 @@ __device__ __forceinline__ void barrier_lds_only() {
 }
 
 // Pinned k loop shared by both operand layouts.  Ops supplies
+//   G                     the WaveGrid
 //   mm(f, n)              MFMA group n (0..kIB*kJB-1) on fragment set f
 //   rd(stage, ks, f, n)   fetch of fragment n (0..kIB+kJB-1) of sub-step ks of `stage` into set f
 //   ld(stage, d)          direct load d (0..2*kLoadsPerWave-1) of the next k-step not yet requested
 // and the loop guarantees: loads of one k-step are requested in order d = 0, 1, ...; a stage is only
 // overwritten after the barrier that follows its last read; a workgroup barrier separates the last
 // LDS read from the return, so the caller may reuse the buffer at once.
-constexpr int kMmPerSub = kIB * kJB;              // 8
-constexpr int kRdPerSub = kIB + kJB;              // 6
-constexpr int kLdPerStep = 2 * kLoadsPerWave;     // 8
-constexpr int kLdSub3 = kLdPerStep * 3 / 8;       // requested in sub-step 3 of the step two ahead
-constexpr int kLdSub0 = kLdPerStep * 3 / 8;       // ... in sub-step 0 of the step before
-constexpr int kLdSub1 = kLdPerStep - kLdSub3 - kLdSub0;
-
 // index of the MFMA after which load k of `cnt` is issued within one sub-step: evenly spread, so
-// that the eight wavefronts of the workgroup do not queue up behind each other at the load unit
-__device__ __forceinline__ constexpr int load_slot(int k, int cnt) {
-  return ((2 * k + 1) * kMmPerSub) / (2 * cnt);
+// that the wavefronts of the workgroup do not queue up behind each other at the load unit
+__device__ __forceinline__ constexpr int load_slot(int k, int cnt, int mm_per_sub) {
+  return ((2 * k + 1) * mm_per_sub) / (2 * cnt);
 }
 
 #define ATG_PIN() __builtin_amdgcn_sched_barrier(0)
@@ -142,6 +165,9 @@ __device__ __forceinline__ constexpr int load_slot(int k, int cnt) {
 // fetched); HAS_NEXT2: step kt+2 exists (its first loads are requested).
 template <bool HAS_NEXT, bool HAS_NEXT2, typename Ops>
 __device__ __forceinline__ void pinned_k_step(Ops& ops, int kt, char* smem) {
+  using G = typename Ops::G;
+  constexpr int kMmPerSub = G::kMmPerSub, kRdPerSub = G::kRdPerSub, kRdEvery = G::kRdEvery;
+  constexpr int kLdSub0 = G::kLdSub0, kLdSub1 = G::kLdSub1, kLdSub3 = G::kLdSub3;
   const int cs = kt & 1;
   const char* cur = smem + cs * kLdsStage;
   const char* nxt = smem + (cs ^ 1) * kLdsStage;
@@ -152,14 +178,14 @@ __device__ __forceinline__ void pinned_k_step(Ops& ops, int kt, char* smem) {
     for (int n = 0; n < kMmPerSub; ++n) {
       ops.mm(f, n);
       ATG_PIN();
-      if (n < kRdPerSub) {
-        ops.rd(cur, ss + 1, f ^ 1, n);
+      if (n % kRdEvery == 0 && n / kRdEvery < kRdPerSub) {
+        ops.rd(cur, ss + 1, f ^ 1, n / kRdEvery);
         ATG_PIN();
       }
       if (HAS_NEXT && ss == 0) {
 #pragma unroll
         for (int k = 0; k < kLdSub0; ++k)
-          if (load_slot(k, kLdSub0) == n) {
+          if (load_slot(k, kLdSub0, kMmPerSub) == n) {
             ops.ld(cs ^ 1, kLdSub3 + k);
             ATG_PIN();
           }
@@ -167,7 +193,7 @@ __device__ __forceinline__ void pinned_k_step(Ops& ops, int kt, char* smem) {
       if (HAS_NEXT && ss == 1) {
 #pragma unroll
         for (int k = 0; k < kLdSub1; ++k)
-          if (load_slot(k, kLdSub1) == n) {
+          if (load_slot(k, kLdSub1, kMmPerSub) == n) {
             ops.ld(cs ^ 1, kLdSub3 + kLdSub0 + k);
             ATG_PIN();
           }
@@ -181,14 +207,14 @@ __device__ __forceinline__ void pinned_k_step(Ops& ops, int kt, char* smem) {
   for (int n = 0; n < kMmPerSub; ++n) {
     ops.mm(1, n);
     ATG_PIN();
-    if (HAS_NEXT && n < kRdPerSub) {
-      ops.rd(nxt, 0, 0, n);
+    if (HAS_NEXT && n % kRdEvery == 0 && n / kRdEvery < kRdPerSub) {
+      ops.rd(nxt, 0, 0, n / kRdEvery);
       ATG_PIN();
     }
     if (HAS_NEXT2) {
 #pragma unroll
       for (int k = 0; k < kLdSub3; ++k)
-        if (load_slot(k, kLdSub3) == n) {
+        if (load_slot(k, kLdSub3, kMmPerSub) == n) {
           ops.ld(cs, k);
           ATG_PIN();
         }
@@ -198,6 +224,8 @@ __device__ __forceinline__ void pinned_k_step(Ops& ops, int kt, char* smem) {
 
 template <typename Ops>
 __device__ __forceinline__ void pinned_k_loop(Ops& ops, int nk, char* smem) {
+  using G = typename Ops::G;
+  constexpr int kLdPerStep = G::kLdPerStep, kLdSub3 = G::kLdSub3, kRdPerSub = G::kRdPerSub;
   // prologue: all of step 0 and the first loads of step 1, which may still be in flight afterwards
 #pragma unroll
   for (int d = 0; d < kLdPerStep; ++d) ops.ld(0, d);
@@ -224,15 +252,18 @@ __device__ __forceinline__ void pinned_k_loop(Ops& ops, int nk, char* smem) {
 // Runs the k loop of one tile.  a_row_ptr(row) / b_row_ptr(row) return the global address of
 // k = 0 of tile row `row` (0..255); rows past the operand's end must be clamped by the functor
 // to some valid row (the epilogue masks them).  nk = number of 128-byte k steps (may be 0).
-// Every thread of the workgroup must call this.  It ends with a workgroup barrier after the last
-// LDS read, so the caller may reuse the LDS buffer at once.
-template <typename T, typename AF, typename BF>
-__device__ __forceinline__ void gemm_tile(floatx16 (&acc)[kIB][kJB], AF a_row_ptr, BF b_row_ptr, int nk,
+// Every thread of the workgroup (G::kThreads of them) must call this.  It ends with a workgroup barrier
+// after the last LDS read, so the caller may reuse the LDS buffer at once.
+// Fragment n of a sub-step is fetched in the order the MFMAs first need it: block row 0 of A, the block
+// columns of B, then the remaining block rows of A (with two block rows, the order A0 A1 B0.. is kept).
+template <typename T, typename Grid = G8, typename AF, typename BF>
+__device__ __forceinline__ void gemm_tile(floatx16 (&acc)[Grid::kIB][Grid::kJB], AF a_row_ptr, BF b_row_ptr, int nk,
                                           char* smem) {
+  constexpr int kIB = Grid::kIB, kJB = Grid::kJB, kLoadsPerWave = Grid::kLoadsPerWave, kRowsPerWave = Grid::kRowsPerWave;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int wm = wave / kWavesB, wn = wave % kWavesB;
+  const int wm = wave / Grid::kWavesB, wn = wave % Grid::kWavesB;
 
 #pragma unroll
   for (int i = 0; i < kIB; ++i)
@@ -242,7 +273,7 @@ __device__ __forceinline__ void gemm_tile(floatx16 (&acc)[kIB][kJB], AF a_row_pt
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   if (nk <= 0) return;
 
-  // direct-load sources: lane l of load q covers row wave*32 + q*8 + l/8, physical chunk l%8
+  // direct-load sources: lane l of load q covers row wave*kRowsPerWave + q*8 + l/8, physical chunk l%8
   const char* ap[kLoadsPerWave];
   const char* bp[kLoadsPerWave];
 #pragma unroll
@@ -259,19 +290,20 @@ __device__ __forceinline__ void gemm_tile(floatx16 (&acc)[kIB][kJB], AF a_row_pt
   int rd_a[kIB], rd_b[kJB], sw_a[kIB], sw_b[kJB];
 #pragma unroll
   for (int i = 0; i < kIB; ++i) {
-    const int ra = wm * (kTile / kWavesA) + i * 32 + (lane & 31);
+    const int ra = wm * (kTile / Grid::kWavesA) + i * 32 + (lane & 31);
     rd_a[i] = ra * kStepBytes;
     sw_a[i] = swz(ra) << 4;
   }
 #pragma unroll
   for (int j = 0; j < kJB; ++j) {
-    const int rb = wn * (kTile / kWavesB) + j * 32 + (lane & 31);
+    const int rb = wn * (kTile / Grid::kWavesB) + j * 32 + (lane & 31);
     rd_b[j] = kLdsOperand + rb * kStepBytes;
     sw_b[j] = swz(rb) << 4;
   }
   const int half16 = (lane >> 5) << 4;
 
   struct Ops {
+    using G = Grid;
     floatx16 (&acc)[kIB][kJB];
     const char* (&ap)[kLoadsPerWave];
     const char* (&bp)[kLoadsPerWave];
@@ -283,10 +315,22 @@ __device__ __forceinline__ void gemm_tile(floatx16 (&acc)[kIB][kJB], AF a_row_pt
     int half16;
     uint4 fa[2][kIB], fb[2][kJB];
     __device__ __forceinline__ void mm(int f, int n) { Mma<T>::run(fa[f][n / kJB], fb[f][n % kJB], acc[n / kJB][n % kJB]); }
+    __device__ __forceinline__ void rd_frag_a(const char* stage, int cb, int f, int i) {
+      fa[f][i] = *reinterpret_cast<const uint4*>(stage + rd_a[i] + (cb ^ sw_a[i]));
+    }
+    __device__ __forceinline__ void rd_frag_b(const char* stage, int cb, int f, int j) {
+      fb[f][j] = *reinterpret_cast<const uint4*>(stage + rd_b[j] + (cb ^ sw_b[j]));
+    }
     __device__ __forceinline__ void rd(const char* stage, int ks, int f, int n) {
       const int cb = (ks << 5) | half16;
-      if (n < kIB) fa[f][n] = *reinterpret_cast<const uint4*>(stage + rd_a[n] + (cb ^ sw_a[n]));
-      else fb[f][n - kIB] = *reinterpret_cast<const uint4*>(stage + rd_b[n - kIB] + (cb ^ sw_b[n - kIB]));
+      if (kIB == 2) {
+        if (n < kIB) rd_frag_a(stage, cb, f, n);
+        else rd_frag_b(stage, cb, f, n - kIB);
+      } else {
+        if (n == 0) rd_frag_a(stage, cb, f, 0);
+        else if (n <= kJB) rd_frag_b(stage, cb, f, n - 1);
+        else rd_frag_a(stage, cb, f, n - kJB);
+      }
     }
     __device__ __forceinline__ void ld(int stage, int d) {
       const uint32_t base = wave_lds + stage * kLdsStage;
@@ -327,9 +371,12 @@ __device__ __forceinline__ uint2 lds_read_tr16(const char* p) {
 // a0 / b0: address of element [k = 0][first column of the tile]; a_ld / b_ld: row strides in bytes;
 // a_cmax / b_cmax: last 16-byte column chunk (0..31) that may be read (columns past it are fetched from
 // that chunk instead and must be masked by the caller); nk: number of 64-row k-steps.
-__device__ __forceinline__ void gemm_tile_kmajor(floatx16 (&acc)[kIB][kJB], const char* a0, size_t a_ld,
+template <typename Grid = G8>
+__device__ __forceinline__ void gemm_tile_kmajor(floatx16 (&acc)[Grid::kIB][Grid::kJB], const char* a0, size_t a_ld,
                                                  int a_cmax, const char* b0, size_t b_ld, int b_cmax, int nk,
                                                  char* smem) {
+  constexpr int kIB = Grid::kIB, kJB = Grid::kJB, kLoadsPerWave = Grid::kLoadsPerWave;
+  constexpr int kWavesA = Grid::kWavesA, kWavesB = Grid::kWavesB;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
@@ -376,6 +423,7 @@ __device__ __forceinline__ void gemm_tile_kmajor(floatx16 (&acc)[kIB][kJB], cons
   }
 
   struct Ops {
+    using G = Grid;
     floatx16 (&acc)[kIB][kJB];
     const char* (&ap)[kLoadsPerWave];
     const char* (&bp)[kLoadsPerWave];
@@ -388,12 +436,22 @@ __device__ __forceinline__ void gemm_tile_kmajor(floatx16 (&acc)[kIB][kJB], cons
       Mma<bf16_t>::run(fa[f][n / kJB], fb[f][n % kJB], acc[n / kJB][n % kJB]);
     }
     __device__ __forceinline__ void rd(const char* stage, int ks, int f, int n) {
-      const char* p = stage + ks * 16 * kKmRowBytes + (n < kIB ? rd_a[n % kIB] : rd_b[(n + kJB - kIB) % kJB]);
+      // fragment order as in gemm_tile
+      bool is_a;
+      int k;
+      if (kIB == 2) {
+        is_a = n < kIB;
+        k = is_a ? n : n - kIB;
+      } else {
+        is_a = n == 0 || n > kJB;
+        k = n == 0 ? 0 : (n <= kJB ? n - 1 : n - kJB);
+      }
+      const char* p = stage + ks * 16 * kKmRowBytes + (is_a ? rd_a[k % kIB] : rd_b[k % kJB]);
       const uint2 lo = lds_read_tr16(p);
       const uint2 hi = lds_read_tr16(p + 4 * kKmRowBytes);
       const uint4 v = make_uint4(lo.x, lo.y, hi.x, hi.y);
-      if (n < kIB) fa[f][n] = v;
-      else fb[f][n - kIB] = v;
+      if (is_a) fa[f][k % kIB] = v;
+      else fb[f][k % kJB] = v;
     }
     __device__ __forceinline__ void ld(int stage, int d) {
       const uint32_t base = wave_lds + stage * kLdsStage;

@@ -4,7 +4,9 @@
 //   gemm_probe <variant> M N K
 //     nt    C[m][n] = sum_k A[m][k] B[n][k]   gemm_tile of gemm_core.hpp: the loop of the forward, dZ and
 //                                             dHidden kernels (256 x 256 tile, 8 wavefronts, 128-byte k-steps)
-//     km    C[m][n] = sum_k A[k][m] B[k][n]   gemm_tile_kmajor: the loop of the dW kernel
+//     km    C[m][n] = sum_k A[k][m] B[k][n]   gemm_tile_kmajor: the k-major loop (dW)
+//     nt4, km4                                the same loops with 4 wavefronts of 128 x 128 per workgroup
+//                                             (the layout the dHidden and dW kernels use)
 //     wg2   as nt, with a different layout that was tried and rejected: 4-wavefront workgroups on 256 x 128
 //           tiles, 64-byte k-steps in three LDS stages of 24 KiB, two workgroups resident per compute unit (so
 //           that one workgroup's epilogue could overlap the other's MFMAs)
@@ -34,35 +36,36 @@ using namespace atg;
 
 constexpr size_t kClockSlot = (size_t{16} << 20) - 1;   // float index in C where workgroup 0 leaves the clock
 
-__device__ __forceinline__ float sum_acc(floatx16 (&acc)[kIB][kJB]) {
+template <int IB, int JB>
+__device__ __forceinline__ float sum_acc(floatx16 (&acc)[IB][JB]) {
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < kIB; ++i)
+  for (int i = 0; i < IB; ++i)
 #pragma unroll
-    for (int j = 0; j < kJB; ++j)
+    for (int j = 0; j < JB; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s += acc[i][j][r];
   return s;
 }
 
-template <bool KMAJOR>
-__global__ __launch_bounds__(kGemmThreads) void k_probe(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+template <bool KMAJOR, typename G>
+__global__ __launch_bounds__(G::kThreads) void k_probe(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                         float* __restrict__ C, int M, int N, int K, int write_c) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const long long clk0 = clock64(), wall0 = wall_clock64();
   const TileOrder ord{M / kTile, N / kTile, 8};
-  const TileCoord tc;
+  const TileCoordT<G> tc;
   float sink = 0.f;
   for (int t = logical_workgroup(); t < ord.total(); t += gridDim.x) {
     int ta, tb;
     ord.decode(t, &ta, &tb);
-    floatx16 acc[kIB][kJB];
+    floatx16 acc[G::kIB][G::kJB];
     if (KMAJOR) {
-      gemm_tile_kmajor(acc, reinterpret_cast<const char*>(A + ta * kTile), static_cast<size_t>(M) * 2, 31,
+      gemm_tile_kmajor<G>(acc, reinterpret_cast<const char*>(A + ta * kTile), static_cast<size_t>(M) * 2, 31,
                        reinterpret_cast<const char*>(B + tb * kTile), static_cast<size_t>(N) * 2, 31, K / kKmRows, smem);
     } else {
       const size_t row_bytes = static_cast<size_t>(K) * 2;
-      gemm_tile<bf16_t>(
+      gemm_tile<bf16_t, G>(
           acc,
           [&](int row) { return reinterpret_cast<const char*>(A) + static_cast<size_t>(ta * kTile + row) * row_bytes; },
           [&](int row) { return reinterpret_cast<const char*>(B) + static_cast<size_t>(tb * kTile + row) * row_bytes; },
@@ -70,11 +73,11 @@ __global__ __launch_bounds__(kGemmThreads) void k_probe(const bf16_t* __restrict
     }
     if (write_c) {
 #pragma unroll
-      for (int i = 0; i < kIB; ++i)
+      for (int i = 0; i < G::kIB; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r)
 #pragma unroll
-          for (int j = 0; j < kJB; ++j)
+          for (int j = 0; j < G::kJB; ++j)
             C[static_cast<size_t>(ta * kTile + tc.a_row(i, r)) * N + tb * kTile + tc.b_row(j)] = acc[i][j][r];
     } else {
       sink += sum_acc(acc);
@@ -272,8 +275,9 @@ int main(int argc, char** argv) {
   }
   const char* variant = argv[1];
   const int M = atoi(argv[2]), N = atoi(argv[3]), K = atoi(argv[4]);
-  const bool km = !strcmp(variant, "km"), two = !strcmp(variant, "wg2");
-  if (!km && !two && strcmp(variant, "nt")) { printf("unknown variant\n"); return 2; }
+  const bool four = !strcmp(variant, "nt4") || !strcmp(variant, "km4");
+  const bool km = !strcmp(variant, "km") || !strcmp(variant, "km4"), two = !strcmp(variant, "wg2");
+  if (!km && !two && strcmp(variant, "nt") && strcmp(variant, "nt4")) { printf("unknown variant\n"); return 2; }
   if (M % 256 || N % 256 || K % (two ? 32 : 64) || M < 512 || N < 512 || K < 64 || (two && (K / 32) % 3 != 1)) {
     printf("unsupported shape\n");
     return 2;
@@ -291,8 +295,10 @@ int main(int argc, char** argv) {
   CHECK(hipMalloc(&dC, size_t{64} << 20));
   CHECK(hipMemcpy(dA, hA.data(), hA.size() * 2, hipMemcpyHostToDevice));
   CHECK(hipMemcpy(dB, hB.data(), hB.size() * 2, hipMemcpyHostToDevice));
-  kern_t kern = two ? wg2::k_probe : (km ? k_probe<true> : k_probe<false>);
-  const int threads = two ? 256 : kGemmThreads, lds = two ? wg2::kLds : kLdsBytes, grid = two ? 512 : 256;
+  kern_t kern = two ? wg2::k_probe
+                    : four ? (km ? k_probe<true, G4> : k_probe<false, G4>)
+                           : (km ? k_probe<true, G8> : k_probe<false, G8>);
+  const int threads = two ? 256 : (four ? G4::kThreads : G8::kThreads), lds = two ? wg2::kLds : kLdsBytes, grid = two ? 512 : 256;
   CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
   {
     // correctness on the 512 x 512 corner (full K); for km the corner is taken from operands of 512 columns

@@ -207,7 +207,10 @@ def test_full_size_sampled_parity_and_invariants(gpu_device, name):
             say(f"[full] {name}: head {k}: the pairing value is within its own bound (not discriminating here)")
 
     # ---- sampled rows of dW, stage parity: both sides are handed the rollout stand-in's log-probs and
-    # log-sum-exp (inputs like any other), so every token takes the same branch on both sides
+    # log-sum-exp (inputs like any other), so every token takes the same branch on both sides.  The
+    # behaviour-policy log-probs used from here on keep every token at least 5e-3 away from the two clip
+    # thresholds (the few that fall closer are moved by 2e-2), so that the one-pass call, which computes its
+    # own log-probs (within 1e-3 of the stand-in's), also takes the oracle's branch at every token.
     say(f"[full] {name}: backward on the stand-in's log-probs for the sampled dW rows")
     logp_in = (wl.old_logp - wl.noise).contiguous()
     lse_in = wl.engine_lse
@@ -216,15 +219,23 @@ def test_full_size_sampled_parity_and_invariants(gpu_device, name):
     for k in range(cfg.n_heads):                                             # ... and the stand-in agrees with the oracle
         pick, _, _, lp = samples[k]
         assert np.abs(host(logp_in)[pick] - lp).max() <= 1e-3
+    d_in = logp_in - wl.old_logp
+    close = ((d_in - float(lo32)).abs() < 5e-3) | ((d_in - float(hi32)).abs() < 5e-3)
+    old2 = torch.where(close, wl.old_logp + 2e-2, wl.old_logp).contiguous()
+    d2 = logp_in - old2
+    assert float(torch.minimum((d2 - float(lo32)).abs(), (d2 - float(hi32)).abs())[wl.valid].min()) >= 4e-3
+    say(f"[full] {name}: {int((close & wl.valid).sum())} tokens moved away from a threshold")
+    old2_np = host(old2)
     del bwd, dH
     torch.cuda.empty_cache()
-    bwd2 = api.at_grpo_policy_loss_bwd(wl.batch, wl.old_logp, adv_dev, logp_in, lse_in, eps, eps)
+    bwd2 = api.at_grpo_policy_loss_bwd(wl.batch, old2, adv_dev, logp_in, lse_in, eps, eps)
     torch.cuda.synchronize()
     assert api.error_word(bwd2["workspace"]) == 0
     logp_np, lse_np = host(logp_in), host(lse_in).astype(np.float64)
+    dw_refs = {}
     for k in range(cfg.n_heads):
         rows_all = np.nonzero(valid_np & (head_of_tok == k))[0]
-        _, ratio, _, sel = orc.surrogate_terms(logp_np[rows_all], old_np[rows_all], A_tok[rows_all], eps, eps)
+        _, ratio, _, sel = orc.surrogate_terms(logp_np[rows_all], old2_np[rows_all], A_tok[rows_all], eps, eps)
         g_all = -(1.0 / n_valid_head[k]) * A_tok[rows_all] * ratio * sel
         live_k = g_all != 0
         rows, g_rows = rows_all[live_k], g_all[live_k]
@@ -236,5 +247,44 @@ def test_full_size_sampled_parity_and_invariants(gpu_device, name):
         got_rows = host(bwd2["dW"][k][torch.from_numpy(pick_v).to(dev)])
         r = helpers.assert_grad_close(got_rows, ref_rows, 2e-2, f"{name} dW rows of head {k}")
         say(f"[full] {name}: head {k} sampled dW rows: worst row {r[0]:.3e}, worst element {r[1]:.3e}")
+        dw_refs[k] = (pick_v, ref_rows)
+    del bwd2
+    torch.cuda.empty_cache()
+
+    # ---- the call that produces the logits once, at full size, against the same oracle values
+    say(f"[full] {name}: forward + backward from one pass over the logits")
+    step = api.at_grpo_policy_loss_fwd_bwd(wl.batch, old2, adv_dev, eps, eps)
+    torch.cuda.synchronize()
+    assert api.error_word(step["workspace"]) == 0
+    assert np.array_equal(host(step["n_valid"]), ref[2])
+    assert float((step["logp"] - logp_in)[wl.valid].abs().max()) <= 1e-3
+    assert float((step["lse"] - lse_in)[wl.valid].abs().max()) <= 1e-3
+    assert float(step["logp"][~wl.valid].abs().max()) == 0.0 if bool((~wl.valid).any()) else True
+    # clip masks and the loss of the whole batch from the stand-in's log-probs (no token sits near a threshold)
+    ref2 = orc.policy_loss_from_logp(logp_np, old2_np, adv32, st.mask, head_of_tok, resp_of_tok, cfg.n_heads, eps, eps)
+    assert np.array_equal(host(step["clip_mask"]), ref2[1])
+    assert np.all(np.abs(host(step["loss"]) - ref2[0]) <= 2e-2 * np.abs(ref2[0]) + 1e-5)
+    dH1 = step["d_hidden"]
+    dead = (~wl.valid) | (adv_dev[wl.resp_of_tok] == 0) | ((step["clip_mask"] & 4) != 0)
+    assert float(dH1[dead].abs().max()) == 0.0 if bool(dead.any()) else True
+    assert bool((dH1[~dead].abs().amax(dim=1) > 0).all())
+    for k in range(cfg.n_heads):
+        pick, _, h_rows, lp = samples[k]
+        W64 = host(wl.batch.W[k]).astype(np.float64)
+        _, ratio, _, sel = orc.surrogate_terms(logp_np[pick], old2_np[pick], A_tok[pick], eps, eps)
+        g = -(1.0 / n_valid_head[k]) * A_tok[pick] * ratio * sel
+        dh_ref, _ = orc.head_backward_single(h_rows, W64, tok_np[pick], g)
+        del W64
+        got = host(dH1[torch.from_numpy(pick).to(dev)]).astype(np.float64)
+        assert np.all(got[g == 0] == 0)
+        r = helpers.assert_grad_close(got, dh_ref, 2e-2, f"{name} d_hidden rows of head {k} (one pass)")
+        pick_v, ref_rows = dw_refs[k]
+        got_rows = host(step["dW"][k][torch.from_numpy(pick_v).to(dev)])
+        r2 = helpers.assert_grad_close(got_rows, ref_rows, 2e-2, f"{name} dW rows of head {k} (one pass)")
+        say(f"[full] {name}: head {k} one pass: d_hidden worst row {r[0]:.3e}, element {r[1]:.3e}; "
+            f"dW rows worst row {r2[0]:.3e}, element {r2[1]:.3e}")
+        dWk = step["dW"][k]
+        assert float(dWk.sum(dim=0).abs().max()) <= 2e-2 * float(dWk.abs().sum(dim=0).max())
+    del step, dH1
     api.release_workspace()
     torch.cuda.empty_cache()
