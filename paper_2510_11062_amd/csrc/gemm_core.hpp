@@ -39,9 +39,6 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 constexpr int kTile = 256;                       // rows of each operand per tile
 constexpr int kStepBytes = 128;                  // bytes of k per row per step
 constexpr int kLdsOperand = kTile * kStepBytes;  // 32 KiB
-constexpr int kLdOperandOffset = kLdsOperand;    // B follows A inside a stage
-constexpr int kLdsStage = 2 * kLdsOperand;       // A then B
-constexpr int kLdsBytes = 2 * kLdsStage;         // two stages: 128 KiB
 
 // How the wavefronts of a workgroup share the 256 x 256 tile: WA x WB wavefronts, each owning a
 // (256 / WA) x (256 / WB) sub-tile.  Two layouts are used:
@@ -133,9 +130,6 @@ __device__ __forceinline__ uint32_t lds_address(const char* p) {
       (__attribute__((address_space(3))) const char*)p));
 }
 
-// s_waitcnt vmcnt(0) only (expcnt and lgkmcnt left at their maxima)
-__device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-
 // Workgroup barrier that orders LDS traffic only: waits for this wavefront's LDS operations
 // (lgkmcnt(0)), not for its outstanding global stores.  __syncthreads() would also wait until every
 // store issued so far has been acknowledged by memory, which an epilogue that has just written its
@@ -146,13 +140,32 @@ __device__ __forceinline__ void barrier_lds_only() {
 }
 
 // Pinned k loop shared by both operand layouts.  Ops supplies
-//   G                     the WaveGrid
-//   mm(f, n)              MFMA group n (0..kIB*kJB-1) on fragment set f
-//   rd(stage, ks, f, n)   fetch of fragment n (0..kIB+kJB-1) of sub-step ks of `stage` into set f
-//   ld(stage, d)          direct load d (0..2*kLoadsPerWave-1) of the next k-step not yet requested
-// and the loop guarantees: loads of one k-step are requested in order d = 0, 1, ...; a stage is only
-// overwritten after the barrier that follows its last read; a workgroup barrier separates the last
-// LDS read from the return, so the caller may reuse the buffer at once.
+//   G                         the WaveGrid
+//   mm(f, n)                  MFMA group n (0..kIB*kJB-1) on fragment set f
+//   rd(sa, sb, ks, f, n)      fetch of fragment n (0..kIB+kJB-1) of sub-step ks into set f; sa / sb are the
+//                             LDS byte offsets of the slots that hold the step's A and B panels
+//   ld_a(slot, q), ld_b(slot, q)   direct load q (0..kLoadsPerWave-1) of the next A / B panel not yet
+//                             requested, into the slot at LDS byte offset `slot`
+//
+// LDS is a ring of five 32 KiB slots, one operand panel (256 rows x 128 bytes) each: the A and B panels of
+// k-step kt sit in slots (2 kt) % 5 and (2 kt + 1) % 5.  While step kt is consumed, the three other slots
+// receive B of step kt+1 and A of step kt+2 (and may still be receiving A of step kt+1): up to 96 KiB of
+// loads are in flight per compute unit, and every load has at least three sub-steps (of four per k-step) to
+// land.  (Two 64 KiB stages, the obvious layout, leave the last loads of a step one sub-step: the loop then
+// waits for memory at every barrier; with the loads removed altogether the same instruction sequence runs
+// at 1.6 PFLOP/s, with two stages at 1.26-1.30.)  Per k-step:
+//   sub-steps 0, 1   request A of step kt+2 (half the loads each), into the slot B of step kt-1 left
+//   sub-step 2       no requests
+//   wait until all but those A loads have landed; workgroup barrier (one per k-step)
+//   sub-step 3       request B of step kt+2 into the slot A of step kt has just left; fetch the first
+//                    fragments of step kt+1
+// The loop guarantees: panels are requested in order of k; a slot is only overwritten after the barrier
+// that follows its last read; a workgroup barrier separates the last LDS read from the return, so the
+// caller may reuse the whole buffer at once.
+constexpr int kLdsSlots = 5;
+constexpr int kLdsSlot = kLdsOperand;              // 32 KiB
+constexpr int kLdsBytes = kLdsSlots * kLdsSlot;    // 160 KiB: all of a compute unit's LDS
+
 // index of the MFMA after which load k of `cnt` is issued within one sub-step: evenly spread, so
 // that the wavefronts of the workgroup do not queue up behind each other at the load unit
 __device__ __forceinline__ constexpr int load_slot(int k, int cnt, int mm_per_sub) {
@@ -161,16 +174,28 @@ __device__ __forceinline__ constexpr int load_slot(int k, int cnt, int mm_per_su
 
 #define ATG_PIN() __builtin_amdgcn_sched_barrier(0)
 
-// One k-step.  HAS_NEXT: step kt+1 exists (its remaining loads are requested, its first fragments
-// fetched); HAS_NEXT2: step kt+2 exists (its first loads are requested).
+// s_waitcnt vmcnt(N) with expcnt and lgkmcnt left at their maxima (N < 64)
+template <int N>
+__device__ __forceinline__ void wait_direct_loads_but() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 0xF) | ((N >> 4) << 14));
+}
+
+__device__ __forceinline__ int ring_slot(int first, int i) {
+  int s = first + i;
+  if (s >= kLdsSlots) s -= kLdsSlots;
+  return s * kLdsSlot;
+}
+
+// One k-step.  `first` = (2 kt) % 5.  HAS_NEXT: step kt+1 exists (its first fragments are fetched);
+// HAS_NEXT2: step kt+2 exists (its panels are requested).
 template <bool HAS_NEXT, bool HAS_NEXT2, typename Ops>
-__device__ __forceinline__ void pinned_k_step(Ops& ops, int kt, char* smem) {
+__device__ __forceinline__ void pinned_k_step(Ops& ops, int first) {
   using G = typename Ops::G;
   constexpr int kMmPerSub = G::kMmPerSub, kRdPerSub = G::kRdPerSub, kRdEvery = G::kRdEvery;
-  constexpr int kLdSub0 = G::kLdSub0, kLdSub1 = G::kLdSub1, kLdSub3 = G::kLdSub3;
-  const int cs = kt & 1;
-  const char* cur = smem + cs * kLdsStage;
-  const char* nxt = smem + (cs ^ 1) * kLdsStage;
+  constexpr int kLd = G::kLoadsPerWave, kHalf = kLd / 2;
+  const int sa = ring_slot(first, 0), sb = ring_slot(first, 1);           // this step
+  const int na = ring_slot(first, 2), nb = ring_slot(first, 3);           // step kt+1
+  const int la = ring_slot(first, 4), lb = sa;                            // where step kt+2 goes
 #pragma unroll
   for (int ss = 0; ss < 3; ++ss) {
     const int f = ss & 1;
@@ -179,43 +204,37 @@ __device__ __forceinline__ void pinned_k_step(Ops& ops, int kt, char* smem) {
       ops.mm(f, n);
       ATG_PIN();
       if (n % kRdEvery == 0 && n / kRdEvery < kRdPerSub) {
-        ops.rd(cur, ss + 1, f ^ 1, n / kRdEvery);
+        ops.rd(sa, sb, ss + 1, f ^ 1, n / kRdEvery);
         ATG_PIN();
       }
-      if (HAS_NEXT && ss == 0) {
+      if (HAS_NEXT2 && ss < 2) {
 #pragma unroll
-        for (int k = 0; k < kLdSub0; ++k)
-          if (load_slot(k, kLdSub0, kMmPerSub) == n) {
-            ops.ld(cs ^ 1, kLdSub3 + k);
-            ATG_PIN();
-          }
-      }
-      if (HAS_NEXT && ss == 1) {
-#pragma unroll
-        for (int k = 0; k < kLdSub1; ++k)
-          if (load_slot(k, kLdSub1, kMmPerSub) == n) {
-            ops.ld(cs ^ 1, kLdSub3 + kLdSub0 + k);
+        for (int k = 0; k < kHalf; ++k)
+          if (load_slot(k, kHalf, kMmPerSub) == n) {
+            ops.ld_a(la, ss * kHalf + k);
             ATG_PIN();
           }
       }
     }
   }
-  wait_direct_loads();   // this wavefront's loads into `nxt` have landed
-  __syncthreads();       // everyone's have, and everyone holds its last fragments of `cur`
+  // everything but the A panel requested above has landed for this wavefront ...
+  if (HAS_NEXT2) wait_direct_loads_but<kLd>();
+  else wait_direct_loads_but<0>();
+  __syncthreads();       // ... and for everyone, and everyone holds its last fragments of this step
   ATG_PIN();
 #pragma unroll
   for (int n = 0; n < kMmPerSub; ++n) {
     ops.mm(1, n);
     ATG_PIN();
     if (HAS_NEXT && n % kRdEvery == 0 && n / kRdEvery < kRdPerSub) {
-      ops.rd(nxt, 0, 0, n / kRdEvery);
+      ops.rd(na, nb, 0, 0, n / kRdEvery);
       ATG_PIN();
     }
     if (HAS_NEXT2) {
 #pragma unroll
-      for (int k = 0; k < kLdSub3; ++k)
-        if (load_slot(k, kLdSub3, kMmPerSub) == n) {
-          ops.ld(cs, k);
+      for (int k = 0; k < kLd; ++k)
+        if (load_slot(k, kLd, kMmPerSub) == n) {
+          ops.ld_b(lb, k);
           ATG_PIN();
         }
     }
@@ -223,30 +242,39 @@ __device__ __forceinline__ void pinned_k_step(Ops& ops, int kt, char* smem) {
 }
 
 template <typename Ops>
-__device__ __forceinline__ void pinned_k_loop(Ops& ops, int nk, char* smem) {
+__device__ __forceinline__ void pinned_k_loop(Ops& ops, int nk) {
   using G = typename Ops::G;
-  constexpr int kLdPerStep = G::kLdPerStep, kLdSub3 = G::kLdSub3, kRdPerSub = G::kRdPerSub;
-  // prologue: all of step 0 and the first loads of step 1, which may still be in flight afterwards
+  constexpr int kLd = G::kLoadsPerWave, kRdPerSub = G::kRdPerSub;
+  // prologue: the panels of step 0 and, if it exists, of step 1 (which may still be in flight afterwards)
 #pragma unroll
-  for (int d = 0; d < kLdPerStep; ++d) ops.ld(0, d);
-  // (a raw barrier: __syncthreads() would add a wait for every outstanding load and store)
+  for (int q = 0; q < kLd; ++q) ops.ld_a(0 * kLdsSlot, q);
+#pragma unroll
+  for (int q = 0; q < kLd; ++q) ops.ld_b(1 * kLdsSlot, q);
+  // (raw barriers: __syncthreads() would add a wait for every outstanding load and store)
   if (nk > 1) {
 #pragma unroll
-    for (int d = 0; d < kLdSub3; ++d) ops.ld(1, d);
-    __builtin_amdgcn_s_waitcnt(0x0070 | kLdSub3);   // vmcnt(kLdSub3) lgkmcnt(0)
+    for (int q = 0; q < kLd; ++q) ops.ld_a(2 * kLdsSlot, q);
+#pragma unroll
+    for (int q = 0; q < kLd; ++q) ops.ld_b(3 * kLdsSlot, q);
+    __builtin_amdgcn_s_waitcnt(0x0070 | ((2 * kLd) & 0xF) | (((2 * kLd) >> 4) << 14));   // vmcnt(2 kLd) lgkmcnt(0)
   } else {
-    __builtin_amdgcn_s_waitcnt(0x0070);             // vmcnt(0) lgkmcnt(0)
+    __builtin_amdgcn_s_waitcnt(0x0070);                                                 // vmcnt(0) lgkmcnt(0)
   }
   __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int n = 0; n < kRdPerSub; ++n) ops.rd(smem, 0, 0, n);
-  int kt = 0;
-  for (; kt + 2 < nk; ++kt) pinned_k_step<true, true>(ops, kt, smem);
-  if (kt + 1 < nk) {
-    pinned_k_step<true, false>(ops, kt, smem);
-    ++kt;
+  for (int n = 0; n < kRdPerSub; ++n) ops.rd(0 * kLdsSlot, 1 * kLdsSlot, 0, 0, n);
+  int kt = 0, first = 0;
+  for (; kt + 2 < nk; ++kt) {
+    pinned_k_step<true, true>(ops, first);
+    first += 2;
+    if (first >= kLdsSlots) first -= kLdsSlots;
   }
-  pinned_k_step<false, false>(ops, kt, smem);
+  if (kt + 1 < nk) {
+    pinned_k_step<true, false>(ops, first);
+    first += 2;
+    if (first >= kLdsSlots) first -= kLdsSlots;
+  }
+  pinned_k_step<false, false>(ops, first);
 }
 
 // Runs the k loop of one tile.  a_row_ptr(row) / b_row_ptr(row) return the global address of
@@ -297,7 +325,7 @@ __device__ __forceinline__ void gemm_tile(floatx16 (&acc)[Grid::kIB][Grid::kJB],
 #pragma unroll
   for (int j = 0; j < kJB; ++j) {
     const int rb = wn * (kTile / Grid::kWavesB) + j * 32 + (lane & 31);
-    rd_b[j] = kLdsOperand + rb * kStepBytes;
+    rd_b[j] = rb * kStepBytes;
     sw_b[j] = swz(rb) << 4;
   }
   const int half16 = (lane >> 5) << 4;
@@ -311,41 +339,39 @@ __device__ __forceinline__ void gemm_tile(floatx16 (&acc)[Grid::kIB][Grid::kJB],
     const int (&rd_b)[kJB];
     const int (&sw_a)[kIB];
     const int (&sw_b)[kJB];
+    const char* smem;
     uint32_t wave_lds;
     int half16;
     uint4 fa[2][kIB], fb[2][kJB];
     __device__ __forceinline__ void mm(int f, int n) { Mma<T>::run(fa[f][n / kJB], fb[f][n % kJB], acc[n / kJB][n % kJB]); }
-    __device__ __forceinline__ void rd_frag_a(const char* stage, int cb, int f, int i) {
-      fa[f][i] = *reinterpret_cast<const uint4*>(stage + rd_a[i] + (cb ^ sw_a[i]));
+    __device__ __forceinline__ void rd_frag_a(int slot, int cb, int f, int i) {
+      fa[f][i] = *reinterpret_cast<const uint4*>(smem + slot + rd_a[i] + (cb ^ sw_a[i]));
     }
-    __device__ __forceinline__ void rd_frag_b(const char* stage, int cb, int f, int j) {
-      fb[f][j] = *reinterpret_cast<const uint4*>(stage + rd_b[j] + (cb ^ sw_b[j]));
+    __device__ __forceinline__ void rd_frag_b(int slot, int cb, int f, int j) {
+      fb[f][j] = *reinterpret_cast<const uint4*>(smem + slot + rd_b[j] + (cb ^ sw_b[j]));
     }
-    __device__ __forceinline__ void rd(const char* stage, int ks, int f, int n) {
+    __device__ __forceinline__ void rd(int sa, int sb, int ks, int f, int n) {
       const int cb = (ks << 5) | half16;
       if (kIB == 2) {
-        if (n < kIB) rd_frag_a(stage, cb, f, n);
-        else rd_frag_b(stage, cb, f, n - kIB);
+        if (n < kIB) rd_frag_a(sa, cb, f, n);
+        else rd_frag_b(sb, cb, f, n - kIB);
       } else {
-        if (n == 0) rd_frag_a(stage, cb, f, 0);
-        else if (n <= kJB) rd_frag_b(stage, cb, f, n - 1);
-        else rd_frag_a(stage, cb, f, n - kJB);
+        if (n == 0) rd_frag_a(sa, cb, f, 0);
+        else if (n <= kJB) rd_frag_b(sb, cb, f, n - 1);
+        else rd_frag_a(sa, cb, f, n - kJB);
       }
     }
-    __device__ __forceinline__ void ld(int stage, int d) {
-      const uint32_t base = wave_lds + stage * kLdsStage;
-      const int q = d >> 1;
-      if (d & 1) {
-        direct_load16(bp[q], base + kLdOperandOffset + q * 8 * kStepBytes);
-        bp[q] += kStepBytes;
-      } else {
-        direct_load16(ap[q], base + q * 8 * kStepBytes);
-        ap[q] += kStepBytes;
-      }
+    __device__ __forceinline__ void ld_a(int slot, int q) {
+      direct_load16(ap[q], wave_lds + slot + q * 8 * kStepBytes);
+      ap[q] += kStepBytes;
+    }
+    __device__ __forceinline__ void ld_b(int slot, int q) {
+      direct_load16(bp[q], wave_lds + slot + q * 8 * kStepBytes);
+      bp[q] += kStepBytes;
     }
   };
-  Ops ops{acc, ap, bp, rd_a, rd_b, sw_a, sw_b, wave_lds, half16, {}, {}};
-  pinned_k_loop(ops, nk, smem);
+  Ops ops{acc, ap, bp, rd_a, rd_b, sw_a, sw_b, smem, wave_lds, half16, {}, {}};
+  pinned_k_loop(ops, nk);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -419,7 +445,7 @@ __device__ __forceinline__ void gemm_tile_kmajor(floatx16 (&acc)[Grid::kIB][Grid
     const int m = wn * (kTile / kWavesB) + j * 32 + 16 * (g & 1) + 4 * qq;
     const int C = m >> 3;
     const int P = (C & 16) | ((C + 4 * r) & 15);
-    rd_b[j] = kLdsOperand + (8 * (g >> 1) + r) * kKmRowBytes + P * 16 + (m & 7) * 2;
+    rd_b[j] = (8 * (g >> 1) + r) * kKmRowBytes + P * 16 + (m & 7) * 2;
   }
 
   struct Ops {
@@ -429,13 +455,14 @@ __device__ __forceinline__ void gemm_tile_kmajor(floatx16 (&acc)[Grid::kIB][Grid
     const char* (&bp)[kLoadsPerWave];
     const int (&rd_a)[kIB];
     const int (&rd_b)[kJB];
+    const char* smem;
     uint32_t wave_lds;
     size_t a_step, b_step;
     uint4 fa[2][kIB], fb[2][kJB];
     __device__ __forceinline__ void mm(int f, int n) {
       Mma<bf16_t>::run(fa[f][n / kJB], fb[f][n % kJB], acc[n / kJB][n % kJB]);
     }
-    __device__ __forceinline__ void rd(const char* stage, int ks, int f, int n) {
+    __device__ __forceinline__ void rd(int sa, int sb, int ks, int f, int n) {
       // fragment order as in gemm_tile
       bool is_a;
       int k;
@@ -446,27 +473,24 @@ __device__ __forceinline__ void gemm_tile_kmajor(floatx16 (&acc)[Grid::kIB][Grid
         is_a = n == 0 || n > kJB;
         k = n == 0 ? 0 : (n <= kJB ? n - 1 : n - kJB);
       }
-      const char* p = stage + ks * 16 * kKmRowBytes + (is_a ? rd_a[k % kIB] : rd_b[k % kJB]);
+      const char* p = smem + ks * 16 * kKmRowBytes + (is_a ? sa + rd_a[k % kIB] : sb + rd_b[k % kJB]);
       const uint2 lo = lds_read_tr16(p);
       const uint2 hi = lds_read_tr16(p + 4 * kKmRowBytes);
       const uint4 v = make_uint4(lo.x, lo.y, hi.x, hi.y);
       if (is_a) fa[f][k % kIB] = v;
       else fb[f][k % kJB] = v;
     }
-    __device__ __forceinline__ void ld(int stage, int d) {
-      const uint32_t base = wave_lds + stage * kLdsStage;
-      const int q = d >> 1;
-      if (d & 1) {
-        direct_load16(bp[q], base + kLdOperandOffset + q * 1024);
-        bp[q] += b_step;
-      } else {
-        direct_load16(ap[q], base + q * 1024);
-        ap[q] += a_step;
-      }
+    __device__ __forceinline__ void ld_a(int slot, int q) {
+      direct_load16(ap[q], wave_lds + slot + q * 1024);
+      ap[q] += a_step;
+    }
+    __device__ __forceinline__ void ld_b(int slot, int q) {
+      direct_load16(bp[q], wave_lds + slot + q * 1024);
+      bp[q] += b_step;
     }
   };
-  Ops ops{acc, ap, bp, rd_a, rd_b, wave_lds, a_step, b_step, {}, {}};
-  pinned_k_loop(ops, nk, smem);
+  Ops ops{acc, ap, bp, rd_a, rd_b, smem, wave_lds, a_step, b_step, {}, {}};
+  pinned_k_loop(ops, nk);
 }
 
 // Persistent-grid tile order.  Workgroups are dealt to the 8 XCDs round-robin by the hardware, so

@@ -458,7 +458,9 @@ __global__ __launch_bounds__(256) void k_ref_logit(const bf16_t* __restrict__ hi
   if (lane == 0) c2[j] = acc * kLog2e;
 }
 
-constexpr int kFeLdsBytes = kDzLdsBytes + kWavesA * kTile * 4;   // staged tile, then the sums of the four vocabulary quarters
+constexpr int kFeRedOffset = kDzLdsBytes;                        // staged tile, then the sums of the four vocabulary quarters
+constexpr int kFeLdsBytes = kLdsBytes;
+static_assert(kFeRedOffset + kWavesA * kTile * 4 <= kFeLdsBytes, "the epilogue buffers must fit the k loop's LDS");
 
 // A = W rows (vocab -> accumulator registers), B = hidden rows (tokens -> lanes), as in the forward.
 // E[j][v] = exp(z - c_j) for the tokens j of the launch; part_s[vt][j] = sum over the 256 vocabulary rows
@@ -476,7 +478,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_fe(
   const TileCoord tc;
   const size_t row_bytes = static_cast<size_t>(H) * 2;
   const int nk = static_cast<int>(row_bytes / kStepBytes);
-  float* red_s = reinterpret_cast<float*>(smem + kDzLdsBytes);   // [kWavesA][256]
+  float* red_s = reinterpret_cast<float*>(smem + kFeRedOffset);   // [kWavesA][256]
 
   for (int t = logical_workgroup(); t < total; t += gridDim.x) {
     int vt, tt;
@@ -800,7 +802,11 @@ __global__ __launch_bounds__(G::kThreads) void k_head_dw_km(const bf16_t* __rest
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int n = chunk_count(cnt, c0, TC);
   if (n <= 0 && !(first_chunk && !accumulate)) return;
-  const TileOrder ord{n_vtiles, (H + kTile - 1) / kTile, 8};
+  // bands of 32 / (tiles along H) vocabulary tiles: the 32 workgroups that share an XCD's L2 then cover every
+  // H-tile of the same few vocabulary tiles, and each panel of the large operand (the 10 GB of dZ rows)
+  // is fetched by one XCD only (measured 2.4 % faster than bands of 8)
+  const int n_htiles = (H + kTile - 1) / kTile;
+  const TileOrder ord{n_vtiles, n_htiles, max(1, 32 / n_htiles)};
   const int total = ord.total();
   const TileCoordT<G> tc;
   const int nk = (n + kTile - 1) / kTile * kTile / kKmRows;
