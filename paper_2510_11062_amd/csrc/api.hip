@@ -83,6 +83,8 @@ struct Plan {
   float* scale;          // [TC] row factors of the super-chunk
   int32_t* gates;        // one word per launch of the exponentials
   int n_gates;
+  int32_t* live;         // [sub] rows of a launch with a non-zero factor, and their count
+  int32_t* live_cnt;
 };
 
 int check_layout(const at_grpo_batch* b, bool need_tensors) {
@@ -199,6 +201,8 @@ void make_plan(const at_grpo_batch* b, int call, WsAlloc& ws, Plan* p) {
     p->scale = ws.take<float>(static_cast<size_t>(g.TC));
     p->n_gates = M * p->n_chunks * (g.TC / p->sub);
     p->gates = ws.take<int32_t>(static_cast<size_t>(p->n_gates));
+    p->live = ws.take<int32_t>(static_cast<size_t>(g.TC));
+    p->live_cnt = ws.take<int32_t>(64);
   }
   if (bwd) {
     p->coef = step ? nullptr : ws.take<float>(static_cast<size_t>(n_tok));
@@ -448,7 +452,7 @@ extern "C" int at_grpo_policy_loss_fwd_bwd(const at_grpo_batch* batch, const flo
         ATG_TRY(launch_ref_logit(gs, sub, batch->hidden, batch->W[m], batch->token_id, p.c2, s));
         ATG_TRY(launch_head_fe(gs, sub, batch->hidden, batch->W[m], batch->token_id, p.c2, E_sub, p.part_s, p.zy, s));
         ATG_TRY(launch_fe_combine(gs, sub, m, p.part_s, p.c2, p.zy, batch->token_id, ca, logp, lse, scale_sub,
-                                  E_sub, gate, s));
+                                  E_sub, gate, c1 == 0 ? p.live_cnt : nullptr, s));
         // exponent range exceeded somewhere in this launch: the two-pass kernels redo it (they return at once
         // otherwise)
         ATG_TRY(launch_head_fwd(gs, sub, batch->hidden, batch->W[m], batch->token_id, p.part_m, p.part_s, nullptr,
@@ -457,8 +461,11 @@ extern "C" int at_grpo_policy_loss_fwd_bwd(const at_grpo_batch* batch, const flo
         ATG_TRY(launch_fallback_scale(gs, sub, m, ca, logp, scale_sub, gate, s));
         ATG_TRY(launch_head_dz(gs, sub, batch->hidden, batch->W[m], batch->token_id, lse, nullptr, E_sub, nullptr, s,
                                gate));
-        ATG_TRY(launch_head_dh(gs, sub, E_sub, p.Wt, d_hidden, s, scale_sub));
       }
+      // rows on the clipped branch (factor 0) stay out of the dHidden contraction (d_hidden is zero there
+      // already); one launch over the whole super-chunk, so that the rows left fill the grid evenly
+      ATG_TRY(launch_live_rows(p.g, ch, p.scale, p.live, p.live_cnt, s));
+      ATG_TRY(launch_head_dh(p.g, ch, p.dZ, p.Wt, d_hidden, s, p.scale, p.live, p.live_cnt));
       ATG_TRY(launch_gather_transpose_hidden(p.g, ch, batch->hidden, p.hT, s, p.scale));
       ATG_TRY(launch_head_dw(p.g, ch, p.dZ, nullptr, p.hT, dW[m], (accumulate_dW != 0 || c > 0) ? 1 : 0,
                              c == 0 ? 1 : 0, s));

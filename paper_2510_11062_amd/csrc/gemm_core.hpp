@@ -1,30 +1,29 @@
 // Workgroup-tile contraction on the gfx950 matrix cores.
 //
-// One 512-thread workgroup (8 wavefronts, 4 x 2, two per SIMD) produces a 256 x 256 fp32 tile
+// One workgroup produces a 256 x 256 fp32 tile
 //   C[a, b] = sum_k A[a, k] * B[b, k]
-// from two operands that are both contiguous along k ("NT" layout).  Each wavefront owns a
-// 64 x 128 sub-tile held as 2 x 4 MFMA 32x32 accumulator blocks (128 accumulator registers per
-// lane).  k is consumed in steps of 128 bytes per row (64 bf16 or 32 fp32 elements).
+// from two operands that are both contiguous along k ("NT" layout; a second entry point takes both
+// operands k-major).  Its wavefronts share the tile as a WaveGrid (below): 8 wavefronts of 64 x 128
+// (2 x 4 MFMA 32x32 accumulator blocks, 128 accumulator registers per lane) or 4 wavefronts of 128 x 128
+// (4 x 4 blocks, 256 registers).  k is consumed in steps of 128 bytes per row (64 bf16 or 32 fp32 elements).
 //
 // Data path: global -> LDS with direct-to-LDS loads (global_load_lds_dwordx4, 16 bytes per lane,
-// one instruction fills 8 rows x 128 bytes), two LDS stages; LDS -> registers with ds_read_b128,
-// fragments fetched one 16-wide sub-step ahead of the MFMAs that consume them.  The 16-byte chunk
-// index of every row is XOR-swizzled (applied on the global side of the direct loads, since their
-// LDS side is fixed to lane * 16) so that the fragment reads are free of bank conflicts.  The direct
-// loads are issued through inline asm: the compiler would otherwise make every later LDS read wait
-// for all outstanding direct loads.  Their completion is enforced by hand with s_waitcnt vmcnt in
-// front of the one workgroup barrier per k-step.
+// one instruction fills 8 rows x 128 bytes) into a ring of five 32 KiB slots (one operand panel each);
+// LDS -> registers with ds_read_b128, fragments fetched one 16-wide sub-step ahead of the MFMAs that
+// consume them.  The 16-byte chunk index of every row is XOR-swizzled (applied on the global side of the
+// direct loads, since their LDS side is fixed to lane * 16) so that the fragment reads are free of bank
+// conflicts.  The direct loads are issued through inline asm: the compiler would otherwise make every
+// later LDS read wait for all outstanding direct loads.  Their completion is enforced by hand with
+// s_waitcnt vmcnt in front of the one workgroup barrier per k-step.
 //
 // Instruction order: a wavefront that issues a burst of LDS reads or direct loads keeps its SIMD's
-// matrix pipe idle for the length of the burst (both wavefronts of a SIMD run in step, so the other
+// matrix pipe idle for the length of the burst (wavefronts that share a SIMD run in step, so the other
 // one rarely fills the gap).  The loop body is therefore written out as a fixed sequence, pinned with
 // scheduling barriers, in which every MFMA is followed by at most one LDS read and one direct load:
-// each memory instruction issues in the shadow of an MFMA that is already executing.  The 8 direct
-// loads a wavefront contributes to k-step kt+2 (stage kt & 1) are spread over the last sub-step of
-// step kt (3 loads, after the barrier that frees the stage) and the first two sub-steps of step
-// kt+1 (3 + 2); they must have landed at the barrier that ends sub-step 2 of step kt+1.
+// each memory instruction issues in the shadow of an MFMA that is already executing.  When which panel
+// is requested is described at pinned_k_step.
 //
-// Accumulator layout (per lane, block (i, j), register r = 0..15):
+// Accumulator layout (per lane, block (i, j), register r = 0..15; 8-wavefront grid):
 //   a = wm*64 + i*32 + 8*(r/4) + 4*(lane/32) + (r%4)        (A row inside the tile)
 //   b = wn*128 + j*32 + lane%32                              (B row inside the tile)
 #pragma once
@@ -60,10 +59,6 @@ struct WaveGrid {
   static constexpr int kMmPerSub = kIB * kJB;              // MFMA groups per 16-wide sub-step
   static constexpr int kRdPerSub = kIB + kJB;              // fragment reads per sub-step
   static constexpr int kRdEvery = kMmPerSub / kRdPerSub;   // a fragment read follows every kRdEvery-th MFMA
-  static constexpr int kLdPerStep = 2 * kLoadsPerWave;     // direct loads per k-step
-  static constexpr int kLdSub3 = kLdPerStep * 3 / 8;       // requested in sub-step 3 of the step two ahead
-  static constexpr int kLdSub0 = kLdPerStep * 3 / 8;       // ... in sub-step 0 of the step before
-  static constexpr int kLdSub1 = kLdPerStep - kLdSub3 - kLdSub0;
 };
 using G8 = WaveGrid<4, 2>;
 using G4 = WaveGrid<2, 2>;

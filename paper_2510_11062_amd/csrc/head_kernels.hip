@@ -615,8 +615,9 @@ __global__ __launch_bounds__(256) void k_fe_combine(const int32_t* __restrict__ 
                                                     const int32_t* __restrict__ token_id, CoefArgs ca,
                                                     float* __restrict__ logp, float* __restrict__ lse,
                                                     float* __restrict__ scale, bf16_t* __restrict__ E, int Vp,
-                                                    int32_t* __restrict__ gate) {
+                                                    int32_t* __restrict__ gate, int32_t* __restrict__ live_cnt) {
   __shared__ float ss[4][64];
+  if (live_cnt && blockIdx.x == 0 && threadIdx.x == 0) *live_cnt = 0;   // the list of live rows is rebuilt afterwards
   const int n = chunk_count(cnt, c0, TC);
   const int tx = threadIdx.x & 63, py = threadIdx.x >> 6;
   const int j = blockIdx.x * 64 + tx;
@@ -656,6 +657,27 @@ __global__ __launch_bounds__(256) void k_fallback_scale(const int32_t* __restric
   scale[j] = -coef_value(ca, head, row, logp[row]);
 }
 
+// live[0 .. *live_cnt) = the rows j of the launch whose factor scale[j] is not zero: rows on the clipped
+// branch of Eq. (2) carry no gradient and are left out of the dHidden contraction.  Each workgroup appends
+// the live rows among its 256 (in order) at a position it reserves with one atomic add, so the list is
+// ordered inside blocks of 256 rows only; dHidden treats every row on its own, so the order of the list
+// does not reach the results.  *live_cnt must be 0 at the start (k_fe_combine clears it).
+__global__ __launch_bounds__(256) void k_live_rows(const int32_t* __restrict__ cnt, int c0, int TC,
+                                                   const float* __restrict__ scale, int32_t* __restrict__ live,
+                                                   int32_t* __restrict__ live_cnt) {
+  __shared__ int lds4[4];
+  __shared__ int base;
+  const int n = chunk_count(cnt, c0, TC);
+  if (blockIdx.x * 256 >= n) return;
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  const int on = (j < n && scale[j] != 0.f) ? 1 : 0;
+  int total;
+  const int pos = block_exclusive_scan_256(on, lds4, &total);
+  if (threadIdx.x == 0) base = total > 0 ? atomicAdd(live_cnt, total) : 0;
+  __syncthreads();
+  if (on) live[base + pos] = j;
+}
+
 // ------------------------------------------------------------------------------------------------
 // dHidden: A = dZ rows (tokens -> registers), B = Wt rows (h -> lanes), k = vocab
 // ------------------------------------------------------------------------------------------------
@@ -665,9 +687,12 @@ __global__ __launch_bounds__(G::kThreads) void k_head_dh(const T* __restrict__ d
                                                           const int32_t* __restrict__ idx,
                                                           const int32_t* __restrict__ cnt, int c0,
                                                           T* __restrict__ d_hidden, int H, int Vp,
-                                                          int TC, const float* __restrict__ scale) {
+                                                          int TC, const float* __restrict__ scale,
+                                                          const int32_t* __restrict__ live,
+                                                          const int32_t* __restrict__ live_cnt) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int n = chunk_count(cnt, c0, TC);
+  // with a list of live rows, tile row j stands for row live[j] of the launch
+  const int n = live ? min(*live_cnt, chunk_count(cnt, c0, TC)) : chunk_count(cnt, c0, TC);
   if (n <= 0) return;
   const TileOrder ord{(n + kTile - 1) / kTile, (H + kTile - 1) / kTile, 8};
   const int total = ord.total();
@@ -682,7 +707,11 @@ __global__ __launch_bounds__(G::kThreads) void k_head_dh(const T* __restrict__ d
     floatx16 acc[G::kIB][G::kJB];
     gemm_tile<T, G>(
         acc,
-        [&](int row) { return reinterpret_cast<const char*>(dZ) + static_cast<size_t>(t0 + row) * row_bytes; },
+        [&](int row) {
+          // rows past the count of a ragged last tile read some valid row (never stored)
+          const int j = live ? live[min(t0 + row, n - 1)] : t0 + row;
+          return reinterpret_cast<const char*>(dZ) + static_cast<size_t>(j) * row_bytes;
+        },
         [&](int row) {
           const int h = min(h0 + row, H - 1);
           return reinterpret_cast<const char*>(Wt) + static_cast<size_t>(h) * row_bytes;
@@ -692,8 +721,9 @@ __global__ __launch_bounds__(G::kThreads) void k_head_dh(const T* __restrict__ d
     for (int i = 0; i < G::kIB; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int j = t0 + tc.a_row(i, r);
-        if (j >= n) continue;
+        const int jt = t0 + tc.a_row(i, r);
+        if (jt >= n) continue;
+        const int j = live ? live[jt] : jt;
         T* out = d_hidden + static_cast<size_t>(idx[c0 + j]) * H;
         const float sc = scale ? scale[j] : 1.f;     // row factor of the one-pass path
 #pragma unroll
@@ -971,10 +1001,11 @@ int launch_head_fe(const HeadGeom& g, const HeadChunk& ch, const void* hidden, c
 
 int launch_fe_combine(const HeadGeom& g, const HeadChunk& ch, int head, const float* part_s, const float* c2,
                       const float* zy, const int32_t* token_id, const CoefArgs& ca, float* logp, float* lse,
-                      float* scale, void* E, int32_t* gate, hipStream_t s) {
+                      float* scale, void* E, int32_t* gate, int32_t* live_cnt, hipStream_t s) {
   ProfScope ps(PROF_LSE_COMBINE, s);
   hipLaunchKernelGGL(k_fe_combine, dim3(g.TC / 64), dim3(256), 0, s, ch.idx, ch.cnt, ch.c0, g.TC, g.n_vtiles,
-                     head, part_s, c2, zy, token_id, ca, logp, lse, scale, static_cast<bf16_t*>(E), g.Vp, gate);
+                     head, part_s, c2, zy, token_id, ca, logp, lse, scale, static_cast<bf16_t*>(E), g.Vp, gate,
+                     live_cnt);
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }
@@ -988,21 +1019,29 @@ int launch_fallback_scale(const HeadGeom& g, const HeadChunk& ch, int head, cons
   return AT_GRPO_OK;
 }
 
+int launch_live_rows(const HeadGeom& g, const HeadChunk& ch, const float* scale, int32_t* live, int32_t* live_cnt,
+                     hipStream_t s) {
+  ProfScope ps(PROF_COEF, s);
+  hipLaunchKernelGGL(k_live_rows, dim3(g.TC / 256), dim3(256), 0, s, ch.cnt, ch.c0, g.TC, scale, live, live_cnt);
+  ATG_LAUNCH_CHECK();
+  return AT_GRPO_OK;
+}
+
 int launch_head_dh(const HeadGeom& g, const HeadChunk& ch, const void* dZ, const void* Wt, void* d_hidden,
-                   hipStream_t s, const float* scale) {
+                   hipStream_t s, const float* scale, const int32_t* live, const int32_t* live_cnt) {
   ProfScope ps(PROF_HEAD_DH, s);
   if (g.dtype == AT_GRPO_BF16) {
     auto k = k_head_dh<bf16_t, G4>;   // k = vocabulary: long loop, 4 wavefronts of 128 x 128
     ATG_TRY(allow_big_lds(k));
     hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(G4::kThreads), kLdsBytes, s,
                        static_cast<const bf16_t*>(dZ), static_cast<const bf16_t*>(Wt), ch.idx, ch.cnt, ch.c0,
-                       static_cast<bf16_t*>(d_hidden), g.H, g.Vp, g.TC, scale);
+                       static_cast<bf16_t*>(d_hidden), g.H, g.Vp, g.TC, scale, live, live_cnt);
   } else {
     auto k = k_head_dh<float, G8>;
     ATG_TRY(allow_big_lds(k));
     hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
                        static_cast<const float*>(dZ), static_cast<const float*>(Wt), ch.idx, ch.cnt, ch.c0,
-                       static_cast<float*>(d_hidden), g.H, g.Vp, g.TC, scale);
+                       static_cast<float*>(d_hidden), g.H, g.Vp, g.TC, scale, live, live_cnt);
   }
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;

@@ -64,19 +64,26 @@ int launch_head_fe(const HeadGeom& g, const HeadChunk& ch, const void* hidden, c
                    const int32_t* token_id, const float* c2, void* E, float* part_s, float* zy, hipStream_t s);
 
 // logp / lse of the rows; scale[j] = -g_j / S_j; E[j][y_j] = e_y - S_j; raises *gate when a row's sum is
-// out of range (that row gets scale 0).
+// out of range (that row gets scale 0); clears *live_cnt for launch_live_rows.
 int launch_fe_combine(const HeadGeom& g, const HeadChunk& ch, int head, const float* part_s, const float* c2,
                       const float* zy, const int32_t* token_id, const CoefArgs& ca, float* logp, float* lse,
-                      float* scale, void* E, int32_t* gate, hipStream_t s);
+                      float* scale, void* E, int32_t* gate, int32_t* live_cnt, hipStream_t s);
 
 // Runs only while *gate != 0: scale[j] = -g_j from logp (E then holds softmax - onehot).
 int launch_fallback_scale(const HeadGeom& g, const HeadChunk& ch, int head, const CoefArgs& ca, const float* logp,
                           float* scale, const int32_t* gate, hipStream_t s);
 
 // d_hidden[row] = dZ[j] . Wt^T for the rows of this super-chunk.
-// With `scale`, row j of the result is multiplied by scale[j] (j counted from ch.c0).
+// With `scale`, row j of the result is multiplied by scale[j] (j counted from ch.c0).  With `live`
+// (a list of rows j of the launch and its device-side length), only those rows are contracted and stored.
 int launch_head_dh(const HeadGeom& g, const HeadChunk& ch, const void* dZ, const void* Wt,
-                   void* d_hidden, hipStream_t s, const float* scale = nullptr);
+                   void* d_hidden, hipStream_t s, const float* scale = nullptr, const int32_t* live = nullptr,
+                   const int32_t* live_cnt = nullptr);
+
+// live[0 .. *live_cnt) = rows j of the launch with scale[j] != 0 (ordered inside blocks of 256 rows only);
+// *live_cnt must be 0 beforehand.
+int launch_live_rows(const HeadGeom& g, const HeadChunk& ch, const float* scale, int32_t* live, int32_t* live_cnt,
+                     hipStream_t s);
 
 // dW[V][H] (+)= dZ^T . hidden rows.  first_chunk: runs even for an empty list so that dW is defined.
 int launch_head_dw(const HeadGeom& g, const HeadChunk& ch, const void* dZ, const void* dZt, const void* hT,
