@@ -183,6 +183,10 @@ def run_config(cfg, dev, steps, warmup, path="one_pass"):
         "response_tokens": n_valid, "rows_with_gradient": n_grad, "device_error_word": err, "path": path,
         "executed_flop_per_step": sum(flops.values()),
         "flop_per_step_if_logits_were_recomputed": hv2 * (n_valid + 3 * n_grad),
+        # whole-step rates (every kernel of the step in the denominator): the contractions this path executes, and
+        # the 8 H V per gradient token a path that recomputes the logits in the backward would be credited with
+        "step_tflops_executed": sum(flops.values()) / (elapsed / steps) / 1e12,
+        "step_tflops_if_logits_were_recomputed": hv2 * (n_valid + 3 * n_grad) / (elapsed / steps) / 1e12,
         "roofline": {"bound": "mfma", "kernel": kern, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": recorded_traffic(cfg.name, kern),
                      "flop_per_launch": flops[kern] / max(work_launches, 1),
@@ -258,6 +262,8 @@ def main():
         "config": {"workload": rec["workload"], "rows_with_gradient": rec["rows_with_gradient"],
                    "device_error_word": rec["device_error_word"], "path": rec["path"]},
         "roofline": rec["roofline"],
+        "step_tflops_executed": rec["step_tflops_executed"],
+        "step_tflops_if_logits_were_recomputed": rec["step_tflops_if_logits_were_recomputed"],
         "head_kernel_tflops": rec["head_kernel_tflops"],
         "kernel_ms_per_step": rec["kernel_ms_per_step"],
     }
