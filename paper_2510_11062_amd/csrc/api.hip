@@ -83,8 +83,10 @@ struct Plan {
   float* scale;          // [TC] row factors of the super-chunk
   int32_t* gates;        // one word per launch of the exponentials
   int n_gates;
-  int32_t* live;         // [sub] rows of a launch with a non-zero factor, and their count
-  int32_t* live_cnt;
+  int32_t* perm;         // [TC] list position of the row that sits at each place after the compaction
+  int32_t* holes;        // [TC] scratch of the compaction
+  int32_t* movers;       // [TC]
+  int32_t* live_cnt;     // [0] rows with a non-zero factor, [1] rows moved
 };
 
 int check_layout(const at_grpo_batch* b, bool need_tensors) {
@@ -201,7 +203,9 @@ void make_plan(const at_grpo_batch* b, int call, WsAlloc& ws, Plan* p) {
     p->scale = ws.take<float>(static_cast<size_t>(g.TC));
     p->n_gates = M * p->n_chunks * (g.TC / p->sub);
     p->gates = ws.take<int32_t>(static_cast<size_t>(p->n_gates));
-    p->live = ws.take<int32_t>(static_cast<size_t>(g.TC));
+    p->perm = ws.take<int32_t>(static_cast<size_t>(g.TC));
+    p->holes = ws.take<int32_t>(static_cast<size_t>(g.TC));
+    p->movers = ws.take<int32_t>(static_cast<size_t>(g.TC));
     p->live_cnt = ws.take<int32_t>(64);
   }
   if (bwd) {
@@ -452,7 +456,7 @@ extern "C" int at_grpo_policy_loss_fwd_bwd(const at_grpo_batch* batch, const flo
         ATG_TRY(launch_ref_logit(gs, sub, batch->hidden, batch->W[m], batch->token_id, p.c2, s));
         ATG_TRY(launch_head_fe(gs, sub, batch->hidden, batch->W[m], batch->token_id, p.c2, E_sub, p.part_s, p.zy, s));
         ATG_TRY(launch_fe_combine(gs, sub, m, p.part_s, p.c2, p.zy, batch->token_id, ca, logp, lse, scale_sub,
-                                  E_sub, gate, c1 == 0 ? p.live_cnt : nullptr, s));
+                                  E_sub, gate, s));
         // exponent range exceeded somewhere in this launch: the two-pass kernels redo it (they return at once
         // otherwise)
         ATG_TRY(launch_head_fwd(gs, sub, batch->hidden, batch->W[m], batch->token_id, p.part_m, p.part_s, nullptr,
@@ -462,13 +466,14 @@ extern "C" int at_grpo_policy_loss_fwd_bwd(const at_grpo_batch* batch, const flo
         ATG_TRY(launch_head_dz(gs, sub, batch->hidden, batch->W[m], batch->token_id, lse, nullptr, E_sub, nullptr, s,
                                gate));
       }
-      // rows on the clipped branch (factor 0) stay out of the dHidden contraction (d_hidden is zero there
-      // already); one launch over the whole super-chunk, so that the rows left fill the grid evenly
-      ATG_TRY(launch_live_rows(p.g, ch, p.scale, p.live, p.live_cnt, s));
-      ATG_TRY(launch_head_dh(p.g, ch, p.dZ, p.Wt, d_hidden, s, p.scale, p.live, p.live_cnt));
-      ATG_TRY(launch_gather_transpose_hidden(p.g, ch, batch->hidden, p.hT, s, p.scale));
+      // rows on the clipped branch (factor 0) are taken out of the chunk before the two contractions
+      // (d_hidden is zero there already); one dHidden launch over the whole super-chunk, so that the rows left
+      // fill the grid evenly
+      ATG_TRY(launch_compact_rows(p.g, ch, p.scale, p.dZ, p.perm, p.holes, p.movers, p.live_cnt, p.live_cnt + 1, s));
+      ATG_TRY(launch_head_dh(p.g, ch, p.dZ, p.Wt, d_hidden, s, p.scale, p.perm, p.live_cnt));
+      ATG_TRY(launch_gather_transpose_hidden(p.g, ch, batch->hidden, p.hT, s, p.scale, p.perm, p.live_cnt));
       ATG_TRY(launch_head_dw(p.g, ch, p.dZ, nullptr, p.hT, dW[m], (accumulate_dW != 0 || c > 0) ? 1 : 0,
-                             c == 0 ? 1 : 0, s));
+                             c == 0 ? 1 : 0, s, p.live_cnt));
     }
   }
   return launch_surrogate(p.L, p.S, logp, old_logp, adv, eps_low, eps_high, agg, loss, clip_mask, n_valid, s);

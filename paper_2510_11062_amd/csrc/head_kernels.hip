@@ -615,9 +615,8 @@ __global__ __launch_bounds__(256) void k_fe_combine(const int32_t* __restrict__ 
                                                     const int32_t* __restrict__ token_id, CoefArgs ca,
                                                     float* __restrict__ logp, float* __restrict__ lse,
                                                     float* __restrict__ scale, bf16_t* __restrict__ E, int Vp,
-                                                    int32_t* __restrict__ gate, int32_t* __restrict__ live_cnt) {
+                                                    int32_t* __restrict__ gate) {
   __shared__ float ss[4][64];
-  if (live_cnt && blockIdx.x == 0 && threadIdx.x == 0) *live_cnt = 0;   // the list of live rows is rebuilt afterwards
   const int n = chunk_count(cnt, c0, TC);
   const int tx = threadIdx.x & 63, py = threadIdx.x >> 6;
   const int j = blockIdx.x * 64 + tx;
@@ -657,25 +656,96 @@ __global__ __launch_bounds__(256) void k_fallback_scale(const int32_t* __restric
   scale[j] = -coef_value(ca, head, row, logp[row]);
 }
 
-// live[0 .. *live_cnt) = the rows j of the launch whose factor scale[j] is not zero: rows on the clipped
-// branch of Eq. (2) carry no gradient and are left out of the dHidden contraction.  Each workgroup appends
-// the live rows among its 256 (in order) at a position it reserves with one atomic add, so the list is
-// ordered inside blocks of 256 rows only; dHidden treats every row on its own, so the order of the list
-// does not reach the results.  *live_cnt must be 0 at the start (k_fe_combine clears it).
-__global__ __launch_bounds__(256) void k_live_rows(const int32_t* __restrict__ cnt, int c0, int TC,
-                                                   const float* __restrict__ scale, int32_t* __restrict__ live,
-                                                   int32_t* __restrict__ live_cnt) {
-  __shared__ int lds4[4];
-  __shared__ int base;
-  const int n = chunk_count(cnt, c0, TC);
-  if (blockIdx.x * 256 >= n) return;
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  const int on = (j < n && scale[j] != 0.f) ? 1 : 0;
-  int total;
-  const int pos = block_exclusive_scan_256(on, lds4, &total);
-  if (threadIdx.x == 0) base = total > 0 ? atomicAdd(live_cnt, total) : 0;
+// Rows on the clipped branch of Eq. (2) (factor scale[j] == 0) carry no gradient.  They are taken out of the
+// super-chunk before the two backward contractions: with L = number of rows with a non-zero factor, every
+// such row at a position >= L (a "mover", in ascending order) is copied into the i-th position < L whose
+// row has factor 0 (a "hole", in ascending order); afterwards rows 0 .. L-1 of E all carry gradient, and
+// perm[j] names the row of the super-chunk that now sits at position j (its token, its factor).  Only the
+// rows that fill holes move (at most min(L, n - L) of them).  One workgroup of 1024 threads, each owning a
+// run of consecutive rows; sums are taken in a fixed order, so the result does not change from run to run.
+constexpr int kPlanThreads = 1024;
+
+__device__ __forceinline__ int block_exclusive_scan_1024(int v, int* lds16, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int up = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += up;
+  }
   __syncthreads();
-  if (on) live[base + pos] = j;
+  if (lane == 63) lds16[wave] = incl;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kPlanThreads / 64; ++w) {
+    if (w < wave) base += lds16[w];
+    tot += lds16[w];
+  }
+  *total = tot;
+  return base + incl - v;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void k_compact_plan(const int32_t* __restrict__ cnt, int c0, int TC,
+                                                               const float* __restrict__ scale,
+                                                               int32_t* __restrict__ perm, int32_t* __restrict__ holes,
+                                                               int32_t* __restrict__ movers,
+                                                               int32_t* __restrict__ live_cnt,
+                                                               int32_t* __restrict__ pair_cnt) {
+  __shared__ int lds16[kPlanThreads / 64];
+  __shared__ int live_below_L;
+  const int n = chunk_count(cnt, c0, TC);
+  const int per = (TC + kPlanThreads - 1) / kPlanThreads;
+  const int j0 = min(static_cast<int>(threadIdx.x) * per, n), j1 = min(j0 + per, n);
+  int c = 0;
+  for (int j = j0; j < j1; ++j) c += (scale[j] != 0.f);
+  int L;
+  const int before = block_exclusive_scan_1024(c, lds16, &L);   // live rows in front of this thread's run
+  if (threadIdx.x == 0) live_below_L = L;                        // L == n: every row is live
+  __syncthreads();
+  if (j0 <= L && L < j1) {                                       // the thread that owns position L
+    int lb = before;
+    for (int j = j0; j < L; ++j) lb += (scale[j] != 0.f);
+    live_below_L = lb;
+  }
+  __syncthreads();
+  const int LB = live_below_L;                                   // holes = L - LB = movers
+  int lb = before;
+  for (int j = j0; j < j1; ++j) {
+    const bool on = scale[j] != 0.f;
+    if (j < L) {
+      if (on) perm[j] = j;
+      else holes[j - lb] = j;
+    } else if (on) {
+      movers[lb - LB] = j;
+    }
+    lb += on;
+  }
+  __threadfence();
+  __syncthreads();
+  lb = before;
+  for (int j = j0; j < j1 && j < L; ++j) {
+    const bool on = scale[j] != 0.f;
+    if (!on) perm[j] = movers[j - lb];
+    lb += on;
+  }
+  if (threadIdx.x == 0) {
+    *live_cnt = L;
+    *pair_cnt = L - LB;
+  }
+}
+
+// E[holes[p]][:] = E[movers[p]][:] for p < *pair_cnt; 16 bytes per lane, one row per workgroup at a time
+__global__ __launch_bounds__(256) void k_move_rows(bf16_t* __restrict__ E, int Vp, const int32_t* __restrict__ holes,
+                                                   const int32_t* __restrict__ movers,
+                                                   const int32_t* __restrict__ pair_cnt) {
+  const int m = *pair_cnt;
+  const int chunks = Vp / 8;   // 16-byte pieces per row (Vp is a multiple of 64)
+  for (int p = blockIdx.x; p < m; p += gridDim.x) {
+    const uint4* src = reinterpret_cast<const uint4*>(E + static_cast<size_t>(movers[p]) * Vp);
+    uint4* dst = reinterpret_cast<uint4*>(E + static_cast<size_t>(holes[p]) * Vp);
+    for (int c = threadIdx.x; c < chunks; c += 256) dst[c] = src[c];
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -688,11 +758,11 @@ __global__ __launch_bounds__(G::kThreads) void k_head_dh(const T* __restrict__ d
                                                           const int32_t* __restrict__ cnt, int c0,
                                                           T* __restrict__ d_hidden, int H, int Vp,
                                                           int TC, const float* __restrict__ scale,
-                                                          const int32_t* __restrict__ live,
+                                                          const int32_t* __restrict__ perm,
                                                           const int32_t* __restrict__ live_cnt) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  // with a list of live rows, tile row j stands for row live[j] of the launch
-  const int n = live ? min(*live_cnt, chunk_count(cnt, c0, TC)) : chunk_count(cnt, c0, TC);
+  // after the rows were compacted: the first *live_cnt rows of dZ, row j belonging to list position perm[j]
+  const int n = perm ? min(*live_cnt, chunk_count(cnt, c0, TC)) : chunk_count(cnt, c0, TC);
   if (n <= 0) return;
   const TileOrder ord{(n + kTile - 1) / kTile, (H + kTile - 1) / kTile, 8};
   const int total = ord.total();
@@ -707,11 +777,7 @@ __global__ __launch_bounds__(G::kThreads) void k_head_dh(const T* __restrict__ d
     floatx16 acc[G::kIB][G::kJB];
     gemm_tile<T, G>(
         acc,
-        [&](int row) {
-          // rows past the count of a ragged last tile read some valid row (never stored)
-          const int j = live ? live[min(t0 + row, n - 1)] : t0 + row;
-          return reinterpret_cast<const char*>(dZ) + static_cast<size_t>(j) * row_bytes;
-        },
+        [&](int row) { return reinterpret_cast<const char*>(dZ) + static_cast<size_t>(t0 + row) * row_bytes; },
         [&](int row) {
           const int h = min(h0 + row, H - 1);
           return reinterpret_cast<const char*>(Wt) + static_cast<size_t>(h) * row_bytes;
@@ -723,7 +789,7 @@ __global__ __launch_bounds__(G::kThreads) void k_head_dh(const T* __restrict__ d
       for (int r = 0; r < 16; ++r) {
         const int jt = t0 + tc.a_row(i, r);
         if (jt >= n) continue;
-        const int j = live ? live[jt] : jt;
+        const int j = perm ? perm[jt] : jt;
         T* out = d_hidden + static_cast<size_t>(idx[c0 + j]) * H;
         const float sc = scale ? scale[j] : 1.f;     // row factor of the one-pass path
 #pragma unroll
@@ -793,16 +859,20 @@ __global__ __launch_bounds__(kGemmThreads) void k_head_dw(const T* __restrict__ 
 __global__ __launch_bounds__(256) void k_gather_rows(const bf16_t* __restrict__ hidden,
                                                      const int32_t* __restrict__ idx,
                                                      const int32_t* __restrict__ cnt, int c0, int TC, int H,
-                                                     const float* __restrict__ scale, bf16_t* __restrict__ hG) {
-  const int n = chunk_count(cnt, c0, TC);
+                                                     const float* __restrict__ scale,
+                                                     const int32_t* __restrict__ perm,
+                                                     const int32_t* __restrict__ live_cnt, bf16_t* __restrict__ hG) {
+  // with perm: row j of hG is list position perm[j], for j < *live_cnt
+  const int n = perm ? min(*live_cnt, chunk_count(cnt, c0, TC)) : chunk_count(cnt, c0, TC);
   const int n_pad = (n + kTile - 1) / kTile * kTile;
   const int chunks = H / 8;                       // 16-byte pieces per row
   const int rows_per_block = 256 / 32;
   for (int j = blockIdx.x * rows_per_block + (threadIdx.x >> 5); j < n_pad; j += gridDim.x * rows_per_block) {
-    const uint4* src = (j < n) ? reinterpret_cast<const uint4*>(hidden + static_cast<size_t>(idx[c0 + j]) * H) : nullptr;
+    const int jp = (j < n && perm) ? perm[j] : j;
+    const uint4* src = (j < n) ? reinterpret_cast<const uint4*>(hidden + static_cast<size_t>(idx[c0 + jp]) * H) : nullptr;
     uint4* dst = reinterpret_cast<uint4*>(hG + static_cast<size_t>(j) * H);
     if (src && scale) {
-      const float sc = scale[j];
+      const float sc = scale[jp];
       for (int c = threadIdx.x & 31; c < chunks; c += 32) {
         const uint4 x = src[c];
         const uint32_t xs[4] = {x.x, x.y, x.z, x.w};
@@ -828,9 +898,10 @@ __global__ __launch_bounds__(G::kThreads) void k_head_dw_km(const bf16_t* __rest
                                                              const int32_t* __restrict__ cnt, int c0,
                                                              float* __restrict__ dW, int H, int V, int Vp,
                                                              int TC, int n_vtiles, int accumulate,
-                                                             int first_chunk) {
+                                                             int first_chunk, const int32_t* __restrict__ live_cnt) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int n = chunk_count(cnt, c0, TC);
+  // live_cnt: the rows were compacted, only the first *live_cnt of the chunk take part
+  const int n = live_cnt ? min(*live_cnt, chunk_count(cnt, c0, TC)) : chunk_count(cnt, c0, TC);
   if (n <= 0 && !(first_chunk && !accumulate)) return;
   // bands of 32 / (tiles along H) vocabulary tiles: the 32 workgroups that share an XCD's L2 then cover every
   // H-tile of the same few vocabulary tiles, and each panel of the large operand (the 10 GB of dZ rows)
@@ -936,12 +1007,12 @@ int launch_transpose_w(const HeadGeom& g, const void* W, void* Wt, hipStream_t s
 }
 
 int launch_gather_transpose_hidden(const HeadGeom& g, const HeadChunk& ch, const void* hidden, void* hT,
-                                   hipStream_t s, const float* scale) {
+                                   hipStream_t s, const float* scale, const int32_t* perm, const int32_t* live_cnt) {
   ProfScope ps(PROF_TRANSPOSE, s);
   if (g.dtype == AT_GRPO_BF16) {
     // bf16: plain row gather (the token contraction reads it k-major)
     hipLaunchKernelGGL(k_gather_rows, dim3(2048), dim3(256), 0, s, static_cast<const bf16_t*>(hidden), ch.idx,
-                       ch.cnt, ch.c0, g.TC, g.H, scale, static_cast<bf16_t*>(hT));
+                       ch.cnt, ch.c0, g.TC, g.H, scale, perm, live_cnt, static_cast<bf16_t*>(hT));
   } else {
     dim3 grid(static_cast<unsigned>(g.TC / 64), static_cast<unsigned>(ceil_div(g.H, 64)));
     hipLaunchKernelGGL(k_transpose<float>, grid, dim3(256), 0, s, static_cast<const float*>(hidden),
@@ -1001,11 +1072,10 @@ int launch_head_fe(const HeadGeom& g, const HeadChunk& ch, const void* hidden, c
 
 int launch_fe_combine(const HeadGeom& g, const HeadChunk& ch, int head, const float* part_s, const float* c2,
                       const float* zy, const int32_t* token_id, const CoefArgs& ca, float* logp, float* lse,
-                      float* scale, void* E, int32_t* gate, int32_t* live_cnt, hipStream_t s) {
+                      float* scale, void* E, int32_t* gate, hipStream_t s) {
   ProfScope ps(PROF_LSE_COMBINE, s);
   hipLaunchKernelGGL(k_fe_combine, dim3(g.TC / 64), dim3(256), 0, s, ch.idx, ch.cnt, ch.c0, g.TC, g.n_vtiles,
-                     head, part_s, c2, zy, token_id, ca, logp, lse, scale, static_cast<bf16_t*>(E), g.Vp, gate,
-                     live_cnt);
+                     head, part_s, c2, zy, token_id, ca, logp, lse, scale, static_cast<bf16_t*>(E), g.Vp, gate);
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }
@@ -1019,43 +1089,47 @@ int launch_fallback_scale(const HeadGeom& g, const HeadChunk& ch, int head, cons
   return AT_GRPO_OK;
 }
 
-int launch_live_rows(const HeadGeom& g, const HeadChunk& ch, const float* scale, int32_t* live, int32_t* live_cnt,
-                     hipStream_t s) {
+int launch_compact_rows(const HeadGeom& g, const HeadChunk& ch, const float* scale, void* E, int32_t* perm,
+                        int32_t* holes, int32_t* movers, int32_t* live_cnt, int32_t* pair_cnt, hipStream_t s) {
   ProfScope ps(PROF_COEF, s);
-  hipLaunchKernelGGL(k_live_rows, dim3(g.TC / 256), dim3(256), 0, s, ch.cnt, ch.c0, g.TC, scale, live, live_cnt);
+  if (g.dtype != AT_GRPO_BF16 || g.TC > 32 * kPlanThreads) return AT_GRPO_EUNSUPPORTED;
+  hipLaunchKernelGGL(k_compact_plan, dim3(1), dim3(kPlanThreads), 0, s, ch.cnt, ch.c0, g.TC, scale, perm, holes,
+                     movers, live_cnt, pair_cnt);
+  ATG_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_move_rows, dim3(2048), dim3(256), 0, s, static_cast<bf16_t*>(E), g.Vp, holes, movers, pair_cnt);
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }
 
 int launch_head_dh(const HeadGeom& g, const HeadChunk& ch, const void* dZ, const void* Wt, void* d_hidden,
-                   hipStream_t s, const float* scale, const int32_t* live, const int32_t* live_cnt) {
+                   hipStream_t s, const float* scale, const int32_t* perm, const int32_t* live_cnt) {
   ProfScope ps(PROF_HEAD_DH, s);
   if (g.dtype == AT_GRPO_BF16) {
     auto k = k_head_dh<bf16_t, G4>;   // k = vocabulary: long loop, 4 wavefronts of 128 x 128
     ATG_TRY(allow_big_lds(k));
     hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(G4::kThreads), kLdsBytes, s,
                        static_cast<const bf16_t*>(dZ), static_cast<const bf16_t*>(Wt), ch.idx, ch.cnt, ch.c0,
-                       static_cast<bf16_t*>(d_hidden), g.H, g.Vp, g.TC, scale, live, live_cnt);
+                       static_cast<bf16_t*>(d_hidden), g.H, g.Vp, g.TC, scale, perm, live_cnt);
   } else {
     auto k = k_head_dh<float, G8>;
     ATG_TRY(allow_big_lds(k));
     hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(kGemmThreads), kLdsBytes, s,
                        static_cast<const float*>(dZ), static_cast<const float*>(Wt), ch.idx, ch.cnt, ch.c0,
-                       static_cast<float*>(d_hidden), g.H, g.Vp, g.TC, scale, live, live_cnt);
+                       static_cast<float*>(d_hidden), g.H, g.Vp, g.TC, scale, perm, live_cnt);
   }
   ATG_LAUNCH_CHECK();
   return AT_GRPO_OK;
 }
 
 int launch_head_dw(const HeadGeom& g, const HeadChunk& ch, const void* dZ, const void* dZt, const void* hT,
-                   float* dW, int accumulate, int first_chunk, hipStream_t s) {
+                   float* dW, int accumulate, int first_chunk, hipStream_t s, const int32_t* live_cnt) {
   ProfScope ps(PROF_HEAD_DW, s);
   if (g.dtype == AT_GRPO_BF16) {
     auto k = k_head_dw_km<G8>;        // 8 wavefronts: measured 4 % faster here than the 4-wavefront layout
     ATG_TRY(allow_big_lds(k));
     hipLaunchKernelGGL(k, dim3(gemm_grid()), dim3(G8::kThreads), kLdsBytes, s, static_cast<const bf16_t*>(dZ),
                        static_cast<const bf16_t*>(hT), ch.cnt, ch.c0, dW, g.H, g.V, g.Vp, g.TC, g.n_vtiles,
-                       accumulate, first_chunk);
+                       accumulate, first_chunk, live_cnt);
   } else {
     auto k = k_head_dw<float>;
     ATG_TRY(allow_big_lds(k));
