@@ -178,3 +178,37 @@ def test_one_pass_falls_back_when_the_exponent_range_is_exceeded(gpu_device):
         helpers.assert_grad_close(host(out["dW"][0]), ref["dW"][0], tol["grad_rel"], "dW")
     else:
         say(f"[one-pass range] {int(near.sum())} tokens next to a threshold: dW not compared")
+
+
+@pytest.mark.gpu
+def test_one_pass_is_reproducible_and_independent_of_workspace_contents(gpu_device):
+    """Two runs give identical bits, also when the scratch memory starts out full of NaN patterns: the row
+    compaction pairs holes and movers in a fixed order, no float atomics are used, and every padded region
+    the kernels read is written by them first.  The case has rows on the clipped branch (they are moved out)
+    and rows of zero-advantage responses (they take the log-probability-only kernels)."""
+    cfg = replace(synth.CONFIGS["C5"], name="one-pass-repro", H=128, V=1200, E=6, len_kind="uniform", len_lo=20,
+                  len_hi=90, forced_equal_groups=3, seed=synth.BASE_SEED + 903)
+    c = helpers.build_case(cfg, device=gpu_device)
+    c.old_logp = (c.old_logp + c.noise).astype(np.float32)
+    ref = helpers.oracle_bwd(c)
+    clipped = int(((ref["g"] == 0) & (ref["w"] != 0) & (c.adv[c.resp_of_tok] != 0)).sum())
+    say(f"[one-pass repro] {c.st.n_valid} response tokens, {clipped} on the clipped branch")
+    assert clipped > 50
+    dc = DeviceCase(c, gpu_device)
+
+    def run():
+        out = api.at_grpo_policy_loss_fwd_bwd(dc.batch(), dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip)
+        torch.cuda.synchronize()
+        assert api.error_word(out["workspace"]) == 0
+        return [out[k].clone() for k in ("loss", "logp", "lse", "clip_mask", "n_valid", "d_hidden")] + \
+               [g.clone() for g in out["dW"]]
+
+    first = run()
+    api._workspace(1, gpu_device).fill_(0xFF)
+    second = run()
+    for a, b in zip(first, second):
+        assert torch.equal(a, b)
+    assert all(torch.isfinite(t.float()).all() for t in second)
+    tol = tolerances(cfg)
+    out = dict(zip(("loss", "logp", "lse", "clip_mask", "n_valid", "d_hidden"), second[:6]), dW=second[6:])
+    check_step_against_oracle(out, ref, c, cfg, tol, "one-pass repro")
