@@ -212,3 +212,78 @@ def test_one_pass_is_reproducible_and_independent_of_workspace_contents(gpu_devi
     tol = tolerances(cfg)
     out = dict(zip(("loss", "logp", "lse", "clip_mask", "n_valid", "d_hidden"), second[:6]), dW=second[6:])
     check_step_against_oracle(out, ref, c, cfg, tol, "one-pass repro")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("H,V", [(192, 1001), (64, 130), (320, 8192)])
+@pytest.mark.parametrize("padded", [False, True])
+def test_one_pass_odd_shapes_and_empty_responses(gpu_device, H, V, padded):
+    """Ragged everything: V not a multiple of the 64-wide k padding (or below one tile), H below one tile,
+    responses of length 0 and 1, row counts that are not multiples of 4, three heads, both aggregations."""
+    cfg = replace(synth.CONFIGS["C1"], name=f"one-pass-odd-{H}-{V}", dtype="bf16", H=H, V=V, n_heads=3, E=5, N=3,
+                  T=2, K=3, len_lo=0, len_hi=9, padded=padded, reward_kind="uniform", forced_equal_groups=1,
+                  seed=synth.BASE_SEED + 77 + H)
+    tol = tolerances(cfg)
+    c = helpers.build_case(cfg, device=gpu_device)
+    assert (c.st.lengths == 0).any() and (c.st.lengths == 1).any()
+    c.old_logp = (c.old_logp + 2 * c.noise).astype(np.float32)
+    grad_loss = np.array([1.0, 0.25, 2.0])
+    gl = torch.from_numpy(grad_loss.astype(np.float32)).to(gpu_device)
+    for agg in ("token_mean", "seq_mean_token_mean"):
+        ref = helpers.oracle_bwd(c, agg=agg, grad_loss=grad_loss)
+        dc = DeviceCase(c, gpu_device)
+        out = api.at_grpo_policy_loss_fwd_bwd(dc.batch(), dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip, agg=agg,
+                                              grad_loss=gl)
+        torch.cuda.synchronize()
+        assert api.error_word(out["workspace"]) == 0
+        check_step_against_oracle(out, ref, c, cfg, tol, f"one-pass odd {agg}")
+
+
+@pytest.mark.gpu
+def test_one_pass_degenerate_batches(gpu_device):
+    """A head without tokens, a batch whose advantages are all zero, a fully masked batch, a single row."""
+    cfg = replace(synth.CONFIGS["C1"], name="one-pass-edge", dtype="bf16", H=64, V=512, n_heads=2)
+    c = helpers.build_case(cfg, device=gpu_device)
+    c.st.head_of_agent[:] = 0                           # every agent -> head 0; head 1 stays empty
+    c.resp_of_tok, c.head_of_tok = orc.token_heads(c.st.n_tok, c.st.cu_seqlens, c.st.agent_id, c.st.head_of_agent)
+    c.token_id, c.old_logp = helpers.oracle_rollout_standin(c.hidden, c.W, c.st.mask, c.head_of_tok, c.u, c.noise)
+    ref = helpers.oracle_bwd(c)
+    tol = tolerances(cfg)
+    dc = DeviceCase(c, gpu_device)
+    say("[one-pass edge] empty head")
+    dW = [torch.full((cfg.V, cfg.H), 7.0, device=gpu_device) for _ in range(2)]
+    out = api.at_grpo_policy_loss_fwd_bwd(dc.batch(), dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip, dW=dW)
+    torch.cuda.synchronize()
+    assert host(out["n_valid"]).tolist() == [c.st.n_valid, 0]
+    assert float(out["loss"][1]) == 0.0 and float(out["dW"][1].abs().max()) == 0.0
+    check_step_against_oracle(out, ref, c, cfg, tol, "one-pass edge")
+
+    say("[one-pass edge] all advantages zero: log-probs as the forward call gives them, no gradient at all")
+    zero_adv = torch.zeros_like(dc.adv)
+    fwd = api.at_grpo_policy_loss_fwd(dc.batch(), dc.old_logp, zero_adv, cfg.eps_clip, cfg.eps_clip)
+    dW = [torch.full((cfg.V, cfg.H), 7.0, device=gpu_device) for _ in range(2)]
+    out = api.at_grpo_policy_loss_fwd_bwd(dc.batch(), dc.old_logp, zero_adv, cfg.eps_clip, cfg.eps_clip, dW=dW)
+    torch.cuda.synchronize()
+    assert torch.equal(out["logp"], fwd["logp"]) and torch.equal(out["lse"], fwd["lse"])
+    assert torch.equal(out["clip_mask"], fwd["clip_mask"]) and torch.equal(out["loss"], fwd["loss"])
+    assert float(out["d_hidden"].abs().max()) == 0.0
+    assert all(float(g.abs().max()) == 0.0 for g in out["dW"])
+
+    say("[one-pass edge] all rows masked")
+    dc.mask = torch.zeros(c.st.n_tok, dtype=torch.uint8, device=gpu_device)
+    out = api.at_grpo_policy_loss_fwd_bwd(dc.batch(), dc.old_logp, dc.adv, cfg.eps_clip, cfg.eps_clip)
+    torch.cuda.synchronize()
+    assert host(out["n_valid"]).tolist() == [0, 0] and float(out["loss"].abs().max()) == 0.0
+    assert float(out["logp"].abs().max()) == 0.0 and float(out["d_hidden"].abs().max()) == 0.0
+    assert all(float(g.abs().max()) == 0.0 for g in out["dW"])
+
+    say("[one-pass edge] one row")
+    cfg1 = replace(synth.CONFIGS["C1"], name="one-pass-one-row", dtype="bf16", H=64, V=300, E=1, N=1, T=1, K=1,
+                   len_lo=1, len_hi=1, forced_equal_groups=0)
+    c1 = helpers.build_case(cfg1, device=gpu_device)
+    c1.adv = np.array([0.7], np.float32)            # a singleton group has advantage 0; give the row a gradient
+    ref1 = helpers.oracle_bwd(c1)
+    dc1 = DeviceCase(c1, gpu_device)
+    out = api.at_grpo_policy_loss_fwd_bwd(dc1.batch(), dc1.old_logp, dc1.adv, cfg1.eps_clip, cfg1.eps_clip)
+    torch.cuda.synchronize()
+    check_step_against_oracle(out, ref1, c1, cfg1, tolerances(cfg1), "one-pass one row")
