@@ -235,7 +235,7 @@ def main():
                     help="after the timed steps, copy 1 GiB with torch (known traffic, to scale HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
+        print("bench.py measures one GPU only: the library has no multi-GPU path (run with --gpus 1)",
               file=sys.stderr)
         sys.exit(2)
     if not torch.cuda.is_available():

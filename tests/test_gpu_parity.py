@@ -1,6 +1,6 @@
 """Parity of the HIP library (through its C ABI) against the CPU oracle.
 
-Tolerances (fixed by the benchmark spec):
+Tolerances:
   * integers (group ids, segment offsets, permutations, counts) and clip masks: bit-exact;
   * fp32 path: 1e-4 relative;
   * bf16 path (fp32 accumulation): 1e-2 absolute on log-probs, 2e-2 relative on the loss;
