@@ -56,6 +56,17 @@ def test_workspace_query_and_argument_errors_on_host():
     fwd = lib.at_grpo_workspace_bytes(api.CALL_POLICY_LOSS_FWD, b, 0, 0, 0, 0)
     bwd = lib.at_grpo_workspace_bytes(api.CALL_POLICY_LOSS_BWD, b, 0, 0, 0, 0)
     assert 0 < fwd < bwd < (40 << 30)
+    # the one-pass step needs the backward's buffers plus its lists and partial sums; fp32 runs the two calls
+    step = lib.at_grpo_workspace_bytes(api.CALL_POLICY_LOSS_FWD_BWD, b, 0, 0, 0, 0)
+    assert bwd < step < bwd + (1 << 30)
+    b.dtype = 0
+    f32 = [lib.at_grpo_workspace_bytes(c, b, 0, 0, 0, 0)
+           for c in (api.CALL_POLICY_LOSS_FWD, api.CALL_POLICY_LOSS_BWD, api.CALL_POLICY_LOSS_FWD_BWD)]
+    assert f32[2] == max(f32[0], f32[1]) > 0
+    b.dtype = 1
+    # null outputs of the one-pass call are rejected before anything is launched
+    assert lib.at_grpo_policy_loss_fwd_bwd(b, None, None, 0.2, 0.2, 0, None, None, None, None, None, None, None,
+                                           None, 0, None, 0, None) == 1
     b.H = 2050                       # not a multiple of 64 elements for bf16
     assert lib.at_grpo_workspace_bytes(api.CALL_POLICY_LOSS_FWD, b, 0, 0, 0, 0) == 0
     # null pointers are rejected before anything is launched
