@@ -901,3 +901,34 @@ def test_trajectory_and_parallel_keys_by_brute_force():
     tuples = [(int(st.env_id[r]), int(st.agent_id[r]), int(st.turn_id[r]),
                int(st.sample_id[r]) if st.turn_id[r] > 0 else 0) for r in order]
     assert tuples == sorted(tuples)
+
+
+def test_logit_gradient_from_exponentials_about_any_reference():
+    """The identity the one-pass training step rests on (derivative of Eq. 2 through the log-softmax): for
+    any per-row reference c, with e = exp(z - c) and S = sum_v e,
+        lse = c + ln S   and   g (onehot - softmax(z)) = a (e - S onehot),  a = -g / S,
+    so d_hidden = a (e - S onehot) W and dW = (e - S onehot)^T (a h).  Checked against the oracle's
+    backward on a small case, with c = the target logit (what the kernels use) and with an arbitrary c."""
+    rng = np.random.default_rng(7)
+    n, H, V = 37, 16, 53
+    hidden = rng.standard_normal((n, H))
+    W = rng.standard_normal((V, H)) * 0.7
+    y = rng.integers(0, V, size=n)
+    g = rng.standard_normal(n) * 1e-2
+    g[::5] = 0.0
+    z = orc.head_logits(hidden, W)
+    logp, lse = orc.token_logprob_single(hidden, W, y)
+    dh_ref, dW_ref = orc.head_backward_single(hidden, W, y, g)
+    onehot = np.zeros((n, V))
+    onehot[np.arange(n), y] = 1.0
+    for c in (z[np.arange(n), y], rng.standard_normal(n) * 3.0):
+        e = np.exp(z - c[:, None])
+        S = e.sum(axis=1)
+        assert np.allclose(c + np.log(S), lse, rtol=0, atol=1e-12)
+        a = -g / S
+        Ep = e - S[:, None] * onehot
+        assert np.allclose((a[:, None] * Ep) @ W, dh_ref, rtol=1e-11, atol=1e-14)
+        assert np.allclose(Ep.T @ (a[:, None] * hidden), dW_ref, rtol=1e-11, atol=1e-14)
+    # with the target logit as reference, e is the probability ratio p_v / p_y and S = 1 / p_y
+    e = np.exp(z - z[np.arange(n), y][:, None])
+    assert np.allclose(e.sum(axis=1), np.exp(-logp), rtol=1e-12)
